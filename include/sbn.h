@@ -1,0 +1,252 @@
+/*
+ * sbn.h -- C ABI of libsbn: convolution with fine-grained group-sparse
+ * weights on AMD MI355X (gfx950).
+ *
+ * The method (Section 3.1): a layer's weights W [oc][kh][kw][ic] are replaced
+ * by W~ = W (.) M, where the 0/1 mask M is constant over blocks of `go` output
+ * channels x `gi` input channels (all kh*kw taps of a block share its bit;
+ * Eq. 2).  The sparse kernels skip removed blocks and are otherwise exact
+ * (Algorithm 1).  Before pruning, filters and channels may be rearranged so
+ * that a parent's filter order is its children's channel order (Section 3.4).
+ *
+ * Conventions for every call
+ *   - Return value: 0 on success, a negative SBN_E* code otherwise.  The text
+ *     of the last failure on the calling thread is kept for sbn_last_error().
+ *   - "host" pointers are ordinary CPU memory, borrowed for the call only.
+ *     "device" pointers are HIP device memory on the device the packed layer
+ *     was created for; they stay owned by the caller.
+ *   - Activations are NHWC fp32, contiguous: x[n][h][w][c].  Weights are OHWI
+ *     fp32: w[oc][kh][kw][ic] (Section 3.1; Algorithm 1 "Data").
+ *   - Run calls (sbn_conv*_sparse, sbn_pointwise_chain) launch kernels on the
+ *     stream given (a hipStream_t passed as void*; NULL = the null stream),
+ *     never allocate, never synchronise and return right after the launch.
+ *   - sbn_packed_t / sbn_chain_t are opaque, created by the library and
+ *     released by sbn_free / sbn_chain_free.  A chain borrows its packed
+ *     layers: free the chain first.
+ *   - Single-layer run calls work in PERMUTED channel space: x carries its
+ *     channels in perm_in order and y comes out in perm_out order.  That is
+ *     what makes the rearrangement free at run time (Section 3.4).
+ */
+#ifndef SBN_H
+#define SBN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* error codes */
+#define SBN_OK      0
+#define SBN_EINVAL (-1)  /* NULL pointer or value out of range            */
+#define SBN_ESHAPE (-2)  /* channels not divisible by go/gi, bad chain    */
+#define SBN_EPERM  (-3)  /* an index array is not a permutation           */
+#define SBN_ENOMEM (-4)  /* host or device allocation failed              */
+#define SBN_EHIP   (-5)  /* a HIP call failed; text in sbn_last_error()   */
+#define SBN_ENODEV (-6)  /* packed layer has no device copy (device = -1) */
+
+/* layer kinds */
+#define SBN_CONV1X1 1
+#define SBN_CONV3X3 3
+
+/* activations applied after bias */
+#define SBN_ACT_NONE 0
+#define SBN_ACT_RELU 1
+
+typedef struct sbn_packed sbn_packed_t;
+typedef struct sbn_chain  sbn_chain_t;
+
+/*
+ * One layer to pack.  Blocks are go output channels x gi input channels
+ * (Section 3.2: 4x4 for Conv1x1 and for whole 3x3 kernels of Conv3x3).
+ * Supported: go in {4, 8}; gi in {1, 2, 4, 8}; c_out % go == 0; c_in % gi == 0.
+ */
+typedef struct {
+    int kind;                 /* SBN_CONV1X1 or SBN_CONV3X3                                     */
+    int c_in, c_out;          /* ic, oc                                                          */
+    int go, gi;               /* block = go filters x gi channels                                */
+    int stride, pad;          /* 3x3: stride in {1,2}, pad must be 1.  1x1: must be 1 and 0      */
+    const float*   w;         /* host, OHWI, ORIGINAL channel order                              */
+    const uint8_t* mask;      /* host [c_out/go][c_in/gi] in PERMUTED block coordinates, 1=kept;
+                                 NULL: a block is kept iff one of its weights has nonzero magnitude */
+    const float*   bias;      /* host [c_out], original order; NULL = no bias                    */
+    const int32_t* perm_out;  /* packed filter r is original filter perm_out[r]; NULL = identity */
+    const int32_t* perm_in;   /* packed channel c is original channel perm_in[c]; NULL = identity*/
+    int act;                  /* SBN_ACT_NONE or SBN_ACT_RELU                                    */
+} sbn_layer_desc_t;
+
+/* Text of the last error on this thread ("" if none).  Never NULL. */
+const char* sbn_last_error(void);
+
+/* ------------------------------------------------------------------ offline, host side */
+
+/*
+ * Block importance and magnitude pruning (Section 3.2: l1 norm per block, the
+ * (oc/go)(ic/gi)*rho least important blocks of the layer are removed; Eq. 2).
+ * w_permuted: host OHWI weights already in packed (permuted) order.
+ * kh = kw = 1 for SBN_CONV1X1, 3 for SBN_CONV3X3.
+ * Removed count = floor(n_blocks * sparsity_percent / 100); norms are summed
+ * in fp64 in (filter, ky, kx, channel) order; ties remove the lower
+ * (row-major) block index first.  mask_out: host uint8 [c_out/go][c_in/gi].
+ */
+int sbn_prune_magnitude(const float* w_permuted, int kind, int c_in, int c_out, int go, int gi,
+                        int sparsity_percent, uint8_t* mask_out);
+
+/*
+ * Retained importance of a layer after pruning: the sum of the block norms
+ * that survive sbn_prune_magnitude at this sparsity -- the quantity the
+ * rearrangement of Section 3.4 tries to raise.  Written to *objective_out.
+ */
+int sbn_retained_l1(const float* w_permuted, int kind, int c_in, int c_out, int go, int gi,
+                    int sparsity_percent, double* objective_out);
+
+/*
+ * Whole-network rearrangement for a chain of layers (Section 3.4).
+ * layers[l].w / c_in / c_out / go / gi / kind are read (mask, bias, perms are
+ * ignored).  parent[l] is the index of the layer whose output feeds layer l,
+ * or -1 if layer l reads the network input; a layer has at most one parent
+ * and layers must be listed parents first.  For every layer l the call
+ * searches a filter permutation perm[l] (int32 [c_out], caller-allocated,
+ * perm_per_layer_out[l]) that raises the retained block importance at
+ * `sparsity_percent`, with the layer's channels already ordered by its
+ * parent's result.  The channel permutation of layer l is perm[parent[l]]
+ * (identity for parent -1).  Layers with keep_output_order[l] != 0 get the
+ * identity (use it for the network's last layer unless its consumer absorbs
+ * the order).  keep_output_order may be NULL (= all zero).
+ *
+ * The search is a deterministic, seeded, bounded hill climb over swaps of two
+ * filters of different groups (at most max_iters candidate swaps per layer;
+ * for c_out <= 8 every canonical grouping is enumerated instead); a swap is
+ * kept only if the objective strictly increases, so the result is never worse
+ * than the identity.  Results are in canonical form: filters ascending inside
+ * each group, groups ordered by first filter.
+ */
+int sbn_rearrange(const sbn_layer_desc_t* layers, int n_layers, const int* parent,
+                  const int* keep_output_order, int sparsity_percent, uint64_t seed, int max_iters,
+                  int32_t* const* perm_per_layer_out);
+
+/*
+ * Pack one layer into the group-sparse format (Algorithm 1's "sparse info":
+ * per output group the first input channel of every kept block) and, when
+ * device >= 0, build the device copy on that HIP device.  device = -1 packs on
+ * the host only (sbn_unpack / sbn_export work, run calls return SBN_ENODEV).
+ * Steps: validate -> permute filters/channels/bias -> mask (given or implied)
+ * -> gather kept blocks row by row.  Pruned weights are dropped; kept blocks
+ * are copied bit for bit (signed zeros and denormals included).
+ */
+int sbn_pack(const sbn_layer_desc_t* desc, int device, sbn_packed_t** out);
+
+/*
+ * Exact inverse of sbn_pack: writes the masked weights W~ in ORIGINAL channel
+ * order (host OHWI [c_out][kh][kw][c_in]; removed blocks are +0.0) and, if
+ * mask_out != NULL, the mask in permuted block coordinates.
+ */
+int sbn_unpack(const sbn_packed_t* p, float* w_out, uint8_t* mask_out);
+
+/*
+ * Canonical arrays of the packed format.  Rows are output groups of `go`
+ * filters in packed order; a row's kept blocks are listed by ascending
+ * channel.  Any output pointer may be NULL (skipped).  *nnz_out receives the
+ * number of kept blocks; call once with NULL arrays to size them.
+ *   row_ptr  uint32 [c_out/go + 1]
+ *   kidx     uint16 [nnz]                   first input channel of the block
+ *   vals     float  [nnz][kh][kw][gi][go]
+ *   perm_out int32  [c_out],  perm_in int32 [c_in],  bias float [c_out] (packed order)
+ */
+int sbn_export(const sbn_packed_t* p, uint32_t* row_ptr, uint16_t* kidx, float* vals,
+               int32_t* perm_out, int32_t* perm_in, float* bias, size_t* nnz_out);
+
+/* Shape of a packed layer; any output pointer may be NULL. */
+int sbn_packed_info(const sbn_packed_t* p, int* kind, int* c_in, int* c_out, int* go, int* gi,
+                    int* stride, int* act, int* device);
+
+void sbn_free(sbn_packed_t* p);
+
+/* ------------------------------------------------------------------ on the GPU */
+
+/*
+ * Group-sparse 1x1 convolution (Algorithm 1): for every pixel p and output
+ * group j,  y[p, j*go:(j+1)*go] = act(bias + sum over kept blocks kb of row j
+ * of x[p, kb:kb+gi] . Wblk[j, kb]).  x: device [n][h][w][c_in], y: device
+ * [n][h][w][c_out], both in packed channel order; x and y must not overlap.
+ * n*h*w may be 0 (nothing is launched).  fp32 multiply-add, fp32 accumulate.
+ */
+int sbn_conv1x1_sparse(const sbn_packed_t* p, const float* x, float* y,
+                       int n, int h, int w, void* stream);
+
+/*
+ * Kernel-level group-sparse 3x3 convolution (Section 3.2, Conv3x3
+ * connectivity pruning with gi x go kernels per group): as above with every
+ * kept block carrying its 9 taps; zero padding 1, stride from the descriptor.
+ * x: device [n][h][w][c_in]; y: device [n][oh][ow][c_out], oh = (h-1)/stride+1.
+ */
+int sbn_conv3x3_sparse(const sbn_packed_t* p, const float* x, float* y,
+                       int n, int h, int w, void* stream);
+
+/*
+ * A stack of layers run back to back on one stream (Section 3.4: activations
+ * stay in rearranged channel order between layers; Section 3.5 engine).
+ */
+#define SBN_ITEM_SPARSE  1   /* a packed 1x1 or 3x3 layer                                 */
+#define SBN_ITEM_DW3X3   2   /* dense depthwise 3x3, pad 1, + bias + act                  */
+#define SBN_ITEM_AVGPOOL 3   /* global average over h*w -> 1x1 spatial                    */
+
+typedef struct {
+    int item;                   /* SBN_ITEM_*                                              */
+    const sbn_packed_t* packed; /* SBN_ITEM_SPARSE: the layer (borrowed)                   */
+    int channels;               /* SBN_ITEM_DW3X3: channel count                            */
+    int stride;                 /* SBN_ITEM_DW3X3: 1 or 2                                   */
+    int act;                    /* SBN_ITEM_DW3X3: SBN_ACT_*                                */
+    const float* dw_w;          /* SBN_ITEM_DW3X3: host [channels][3][3], ORIGINAL order    */
+    const float* dw_bias;       /* SBN_ITEM_DW3X3: host [channels] original order or NULL   */
+} sbn_chain_item_t;
+
+/*
+ * Build a chain on `device`.  Checks that channel counts chain and that each
+ * sparse layer's perm_in equals the order its input arrives in (the perm_out
+ * of the nearest sparse layer before it; depthwise and pooling items keep the
+ * order and have their per-channel parameters permuted to match); the first
+ * item must expect the identity order.  SBN_ESHAPE otherwise.
+ */
+int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn_chain_t** out);
+
+/* Bytes of device workspace the chain needs for an input of n x h x w. */
+int sbn_chain_workspace(const sbn_chain_t* c, int n, int h, int w, size_t* bytes_out);
+
+/* Output shape of the chain for an input of n x h x w (any pointer may be NULL). */
+int sbn_chain_output_shape(const sbn_chain_t* c, int n, int h, int w, int* oh, int* ow, int* oc);
+
+/*
+ * Run the chain: x device [n][h][w][c_in of first item], y device
+ * [n][oh][ow][oc] in the last item's channel order.  workspace: device
+ * memory of at least sbn_chain_workspace bytes, 256-byte aligned, used for
+ * the intermediate activations (ping-pong).  If layer_outputs != NULL it is
+ * a host array of n_items device pointers; a non-NULL entry i receives a
+ * copy of item i's output (for per-layer checks), queued on the same stream.
+ */
+int sbn_pointwise_chain(const sbn_chain_t* c, const float* x, float* y, int n, int h, int w,
+                        void* workspace, size_t workspace_bytes, float* const* layer_outputs,
+                        void* stream);
+
+void sbn_chain_free(sbn_chain_t* c);
+
+/* ------------------------------------------------------------------ measurement helpers */
+
+/*
+ * Number of kept blocks and the multiply-adds per output pixel they imply
+ * (go*gi*kh*kw per kept block): the "nonzero FLOPs" of the throughput metric
+ * are 2 * macs_per_pixel * output pixels.
+ */
+int sbn_packed_work(const sbn_packed_t* p, size_t* nnz_blocks_out, size_t* macs_per_pixel_out);
+
+/*
+ * Plain device-to-device copy kernel of `bytes` bytes (multiple of 16), used
+ * to calibrate hardware counters and to measure the attainable HBM rate.
+ */
+int sbn_copy_bytes(const void* src, void* dst, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SBN_H */

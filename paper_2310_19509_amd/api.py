@@ -1,0 +1,278 @@
+"""Argument marshalling for the C ABI (include/sbn.h).  No arithmetic here."""
+from __future__ import annotations
+
+import ctypes as C
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+from . import _lib
+from ._lib import ChainItem, LayerDesc
+
+__all__ = [
+    "SBN_CONV1X1", "SBN_CONV3X3", "SBN_ACT_NONE", "SBN_ACT_RELU",
+    "SBN_ITEM_SPARSE", "SBN_ITEM_DW3X3", "SBN_ITEM_AVGPOOL", "SbnError", "Packed", "Chain",
+    "sbn_last_error", "sbn_prune_magnitude", "sbn_retained_l1", "sbn_rearrange", "sbn_pack", "sbn_unpack",
+    "sbn_export", "sbn_packed_info", "sbn_packed_work", "sbn_free", "sbn_conv1x1_sparse", "sbn_conv3x3_sparse",
+    "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_chain_free",
+    "sbn_copy_bytes", "dw_item", "sparse_item", "avgpool_item",
+]
+
+SBN_CONV1X1, SBN_CONV3X3 = 1, 3
+SBN_ACT_NONE, SBN_ACT_RELU = 0, 1
+SBN_ITEM_SPARSE, SBN_ITEM_DW3X3, SBN_ITEM_AVGPOOL = 1, 2, 3
+
+
+class SbnError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"sbn error {code}: {text}")
+        self.code = code
+
+
+def sbn_last_error() -> str:
+    return _lib.lib().sbn_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise SbnError(rc, sbn_last_error())
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data
+
+
+def _dev_ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (or a raw int address / None)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_cuda and t.is_contiguous() and t.dtype.is_floating_point and t.element_size() == 4
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _taps(kind: int) -> int:
+    return 9 if kind == SBN_CONV3X3 else 1
+
+
+class Packed:
+    """Owner of an sbn_packed_t*; freed on garbage collection or by sbn_free."""
+
+    def __init__(self, handle: int):
+        self.handle = handle
+
+    def __del__(self):
+        try:
+            sbn_free(self)
+        except Exception:
+            pass
+
+
+class Chain:
+    def __init__(self, handle: int, keep):
+        self.handle = handle
+        self._keep = keep
+
+    def __del__(self):
+        try:
+            sbn_chain_free(self)
+        except Exception:
+            pass
+
+
+def _desc(kind, w, go, gi, mask=None, bias=None, perm_out=None, perm_in=None, stride=1, pad=None,
+          act=SBN_ACT_NONE):
+    w = _f32(w)
+    c_out, kh, kw, c_in = w.shape
+    assert kh == kw == (3 if kind == SBN_CONV3X3 else 1)
+    keep = [w]
+    d = LayerDesc()
+    d.kind, d.c_in, d.c_out, d.go, d.gi = kind, c_in, c_out, go, gi
+    d.stride = stride
+    d.pad = (1 if kind == SBN_CONV3X3 else 0) if pad is None else pad
+    d.act = act
+    d.w = w.ctypes.data
+    for name, arr, dt in (("mask", mask, np.uint8), ("bias", bias, np.float32),
+                          ("perm_out", perm_out, np.int32), ("perm_in", perm_in, np.int32)):
+        if arr is not None:
+            a = np.ascontiguousarray(arr, dtype=dt)
+            keep.append(a)
+            setattr(d, name, a.ctypes.data)
+    return d, keep
+
+
+def sbn_prune_magnitude(w_permuted, kind: int, go: int, gi: int, sparsity_percent: int) -> np.ndarray:
+    w = _f32(w_permuted)
+    c_out, _, _, c_in = w.shape
+    mask = np.empty((max(c_out // go, 0), max(c_in // gi, 0)), dtype=np.uint8)
+    _check(_lib.lib().sbn_prune_magnitude(w.ctypes.data, kind, c_in, c_out, go, gi, sparsity_percent,
+                                          mask.ctypes.data))
+    return mask
+
+
+def sbn_retained_l1(w_permuted, kind: int, go: int, gi: int, sparsity_percent: int) -> float:
+    w = _f32(w_permuted)
+    c_out, _, _, c_in = w.shape
+    out = C.c_double()
+    _check(_lib.lib().sbn_retained_l1(w.ctypes.data, kind, c_in, c_out, go, gi, sparsity_percent, C.byref(out)))
+    return out.value
+
+
+def sbn_rearrange(layers: Sequence[dict], parent: Sequence[int], sparsity_percent: int, seed: int = 0,
+                  max_iters: int = 2000, keep_output_order: Optional[Sequence[int]] = None) -> List[np.ndarray]:
+    """layers: dicts with kind, w, go, gi.  Returns one filter permutation per layer."""
+    n = len(layers)
+    descs = (LayerDesc * n)()
+    keep = []
+    for i, l in enumerate(layers):
+        d, k = _desc(l["kind"], l["w"], l["go"], l["gi"])
+        descs[i] = d
+        keep.append(k)
+    par = (C.c_int * n)(*parent)
+    koo = None if keep_output_order is None else (C.c_int * n)(*keep_output_order)
+    perms = [np.empty(descs[i].c_out, dtype=np.int32) for i in range(n)]
+    pp = (C.c_void_p * n)(*[p.ctypes.data for p in perms])
+    _check(_lib.lib().sbn_rearrange(descs, n, par, koo, sparsity_percent, seed, max_iters, pp))
+    return perms
+
+
+def sbn_pack(kind: int, w, go: int, gi: int, mask=None, bias=None, perm_out=None, perm_in=None, stride: int = 1,
+             pad: Optional[int] = None, act: int = SBN_ACT_NONE, device: int = 0) -> Packed:
+    d, keep = _desc(kind, w, go, gi, mask, bias, perm_out, perm_in, stride, pad, act)
+    out = C.c_void_p()
+    _check(_lib.lib().sbn_pack(C.byref(d), device, C.byref(out)))
+    del keep
+    return Packed(out.value)
+
+
+def sbn_packed_info(p: Packed) -> dict:
+    v = [C.c_int() for _ in range(8)]
+    _check(_lib.lib().sbn_packed_info(p.handle, *[C.byref(x) for x in v]))
+    names = ("kind", "c_in", "c_out", "go", "gi", "stride", "act", "device")
+    return {k: x.value for k, x in zip(names, v)}
+
+
+def sbn_packed_work(p: Packed) -> dict:
+    nnz, macs = C.c_size_t(), C.c_size_t()
+    _check(_lib.lib().sbn_packed_work(p.handle, C.byref(nnz), C.byref(macs)))
+    return dict(nnz_blocks=nnz.value, macs_per_pixel=macs.value)
+
+
+def sbn_unpack(p: Packed):
+    """Returns (masked weights OHWI in original order, mask in permuted block coordinates)."""
+    i = sbn_packed_info(p)
+    k = 3 if i["kind"] == SBN_CONV3X3 else 1
+    w = np.empty((i["c_out"], k, k, i["c_in"]), dtype=np.float32)
+    m = np.empty((i["c_out"] // i["go"], i["c_in"] // i["gi"]), dtype=np.uint8)
+    _check(_lib.lib().sbn_unpack(p.handle, w.ctypes.data, m.ctypes.data))
+    return w, m
+
+
+def sbn_export(p: Packed) -> dict:
+    i = sbn_packed_info(p)
+    nnz = C.c_size_t()
+    _check(_lib.lib().sbn_export(p.handle, None, None, None, None, None, None, C.byref(nnz)))
+    k = 3 if i["kind"] == SBN_CONV3X3 else 1
+    row_ptr = np.empty(i["c_out"] // i["go"] + 1, dtype=np.uint32)
+    kidx = np.empty(nnz.value, dtype=np.uint16)
+    vals = np.empty((nnz.value, k, k, i["gi"], i["go"]), dtype=np.float32)
+    perm_out = np.empty(i["c_out"], dtype=np.int32)
+    perm_in = np.empty(i["c_in"], dtype=np.int32)
+    bias = np.empty(i["c_out"], dtype=np.float32)
+    _check(_lib.lib().sbn_export(p.handle, row_ptr.ctypes.data, kidx.ctypes.data, vals.ctypes.data,
+                                 perm_out.ctypes.data, perm_in.ctypes.data, bias.ctypes.data, C.byref(nnz)))
+    return dict(row_ptr=row_ptr, kidx=kidx, vals=vals, perm_out=perm_out, perm_in=perm_in, bias=bias,
+                nnz=nnz.value)
+
+
+def sbn_free(p: Packed) -> None:
+    if p is not None and p.handle:
+        _lib.lib().sbn_free(p.handle)
+        p.handle = None
+
+
+def sbn_conv1x1_sparse(p: Packed, x, y, n: int, h: int, w: int, stream=None) -> None:
+    _check(_lib.lib().sbn_conv1x1_sparse(p.handle, _dev_ptr(x), _dev_ptr(y), n, h, w, _stream(stream)))
+
+
+def sbn_conv3x3_sparse(p: Packed, x, y, n: int, h: int, w: int, stream=None) -> None:
+    _check(_lib.lib().sbn_conv3x3_sparse(p.handle, _dev_ptr(x), _dev_ptr(y), n, h, w, _stream(stream)))
+
+
+def sparse_item(p: Packed) -> dict:
+    return dict(item=SBN_ITEM_SPARSE, packed=p)
+
+
+def dw_item(w, bias=None, stride: int = 1, act: int = SBN_ACT_RELU) -> dict:
+    return dict(item=SBN_ITEM_DW3X3, w=_f32(w), bias=None if bias is None else _f32(bias), stride=stride, act=act)
+
+
+def avgpool_item() -> dict:
+    return dict(item=SBN_ITEM_AVGPOOL)
+
+
+def sbn_chain_create(items: Sequence[dict], device: int = 0) -> Chain:
+    n = len(items)
+    arr = (ChainItem * n)()
+    keep = []
+    for i, it in enumerate(items):
+        arr[i].item = it["item"]
+        if it["item"] == SBN_ITEM_SPARSE:
+            arr[i].packed = it["packed"].handle
+            keep.append(it["packed"])
+        elif it["item"] == SBN_ITEM_DW3X3:
+            arr[i].channels = it["w"].shape[0]
+            arr[i].stride = it["stride"]
+            arr[i].act = it["act"]
+            arr[i].dw_w = it["w"].ctypes.data
+            arr[i].dw_bias = _ptr(it["bias"])
+            keep.append(it)
+    out = C.c_void_p()
+    _check(_lib.lib().sbn_chain_create(arr, n, device, C.byref(out)))
+    return Chain(out.value, keep)
+
+
+def sbn_chain_workspace(c: Chain, n: int, h: int, w: int) -> int:
+    b = C.c_size_t()
+    _check(_lib.lib().sbn_chain_workspace(c.handle, n, h, w, C.byref(b)))
+    return b.value
+
+
+def sbn_chain_output_shape(c: Chain, n: int, h: int, w: int):
+    oh, ow, oc = C.c_int(), C.c_int(), C.c_int()
+    _check(_lib.lib().sbn_chain_output_shape(c.handle, n, h, w, C.byref(oh), C.byref(ow), C.byref(oc)))
+    return oh.value, ow.value, oc.value
+
+
+def sbn_pointwise_chain(c: Chain, x, y, n: int, h: int, w: int, workspace, layer_outputs=None, stream=None) -> None:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    lo = None
+    if layer_outputs is not None:
+        lo = (C.c_void_p * len(layer_outputs))(*[_dev_ptr(t) for t in layer_outputs])
+    _check(_lib.lib().sbn_pointwise_chain(c.handle, _dev_ptr(x), _dev_ptr(y), n, h, w,
+                                          None if workspace is None else workspace.data_ptr(), ws_bytes, lo,
+                                          _stream(stream)))
+
+
+def sbn_chain_free(c: Chain) -> None:
+    if c is not None and c.handle:
+        _lib.lib().sbn_chain_free(c.handle)
+        c.handle = None
+
+
+def sbn_copy_bytes(src, dst, nbytes: int, stream=None) -> None:
+    _check(_lib.lib().sbn_copy_bytes(src.data_ptr(), dst.data_ptr(), nbytes, _stream(stream)))

@@ -1,0 +1,251 @@
+// Layer chaining: a stack of packed sparse layers, optionally interleaved with
+// dense depthwise 3x3 layers and a global average pool, run back to back on
+// one stream with activations kept in rearranged channel order (Section 3.4).
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <new>
+
+#include "sbn_internal.h"
+
+using namespace sbn;
+
+struct sbn_chain {
+    struct Item {
+        int item = 0;
+        const sbn_packed* packed = nullptr;
+        int channels = 0, stride = 1, act = 0;
+        float* d_w = nullptr;      // depthwise: [9][channels] in the arriving channel order
+        float* d_b = nullptr;      // depthwise: [channels]
+    };
+    std::vector<Item> items;
+    int device = 0;
+    int c_in = 0;
+    void* d_blob = nullptr;
+};
+
+namespace {
+
+struct Shape {
+    long long n;
+    int h, w, c;
+    size_t bytes() const { return (size_t)n * h * w * c * sizeof(float); }
+};
+
+Shape next_shape(const sbn_chain::Item& it, Shape s)
+{
+    switch (it.item) {
+    case SBN_ITEM_SPARSE:
+        if (it.packed->kind == SBN_CONV3X3) {
+            s.h = (s.h - 1) / it.packed->stride + 1;
+            s.w = (s.w - 1) / it.packed->stride + 1;
+        }
+        s.c = it.packed->c_out;
+        break;
+    case SBN_ITEM_DW3X3:
+        s.h = (s.h - 1) / it.stride + 1;
+        s.w = (s.w - 1) / it.stride + 1;
+        break;
+    case SBN_ITEM_AVGPOOL:
+        s.h = s.w = 1;
+        break;
+    }
+    return s;
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t max_intermediate(const sbn_chain* c, int n, int h, int w)
+{
+    Shape s{n, h, w, c->c_in};
+    size_t mx = 0;
+    for (size_t i = 0; i + 1 < c->items.size(); ++i) {
+        s = next_shape(c->items[i], s);
+        mx = std::max(mx, s.bytes());
+    }
+    return align256(mx);
+}
+
+}  // namespace
+
+extern "C" {
+
+int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn_chain_t** out)
+{
+    clear_error();
+    if (!items || !out || n_items <= 0) return fail(SBN_EINVAL, "sbn_chain_create: NULL pointer or empty chain");
+    *out = nullptr;
+    if (device < 0) return fail(SBN_EINVAL, "sbn_chain_create: device must be >= 0");
+    sbn_chain* c = new (std::nothrow) sbn_chain;
+    if (!c) return fail(SBN_ENOMEM, "out of host memory");
+    c->device = device;
+
+    std::vector<int32_t> order;      // order[ch] = original channel carried at position ch; empty = identity
+    int cur_c = -1;
+    size_t dw_floats = 0;
+    for (int i = 0; i < n_items; ++i) {
+        const sbn_chain_item_t& s = items[i];
+        sbn_chain::Item it;
+        it.item = s.item;
+        if (s.item == SBN_ITEM_SPARSE) {
+            const sbn_packed* p = s.packed;
+            if (!p) { delete c; return fail(SBN_EINVAL, "chain item %d: packed layer is NULL", i); }
+            if (p->device != device) { delete c; return fail(SBN_EINVAL, "chain item %d lives on device %d, chain on %d", i, p->device, device); }
+            if (cur_c >= 0 && p->c_in != cur_c) { delete c; return fail(SBN_ESHAPE, "chain item %d reads %d channels, previous item writes %d", i, p->c_in, cur_c); }
+            for (int ch = 0; ch < p->c_in; ++ch) {
+                const int32_t want = order.empty() ? ch : order[(size_t)ch];
+                if (p->perm_in[(size_t)ch] != want) {
+                    delete c;
+                    return fail(SBN_ESHAPE, "chain item %d: perm_in[%d] = %d but its input arrives with channel %d there", i, ch, p->perm_in[(size_t)ch], want);
+                }
+            }
+            if (cur_c < 0) c->c_in = p->c_in;
+            it.packed = p;
+            cur_c = p->c_out;
+            order = p->perm_out;
+        } else if (s.item == SBN_ITEM_DW3X3) {
+            if (s.channels <= 0 || s.channels % 4 || !s.dw_w || (s.stride != 1 && s.stride != 2) ||
+                (s.act != SBN_ACT_NONE && s.act != SBN_ACT_RELU)) {
+                delete c;
+                return fail(SBN_EINVAL, "chain item %d: bad depthwise description (channels must be a positive multiple of 4, stride 1 or 2)", i);
+            }
+            if (cur_c >= 0 && s.channels != cur_c) { delete c; return fail(SBN_ESHAPE, "chain item %d has %d channels, previous item writes %d", i, s.channels, cur_c); }
+            if (cur_c < 0) c->c_in = s.channels;
+            it.channels = s.channels;
+            it.stride = s.stride;
+            it.act = s.act;
+            cur_c = s.channels;
+            dw_floats += (size_t)10 * s.channels;
+        } else if (s.item == SBN_ITEM_AVGPOOL) {
+            if (cur_c < 0) { delete c; return fail(SBN_ESHAPE, "a chain cannot start with the average pool"); }
+            it.channels = cur_c;
+        } else {
+            delete c;
+            return fail(SBN_EINVAL, "chain item %d: unknown item kind %d", i, s.item);
+        }
+        c->items.push_back(it);
+    }
+
+    if (dw_floats) {
+        int prev = 0;
+        (void)hipGetDevice(&prev);
+        hipError_t e = hipSetDevice(device);
+        float* blob = nullptr;
+        if (e == hipSuccess) e = hipMalloc((void**)&blob, dw_floats * sizeof(float));
+        if (e != hipSuccess) {
+            (void)hipSetDevice(prev);
+            delete c;
+            return fail(e == hipErrorOutOfMemory ? SBN_ENOMEM : SBN_EHIP, "chain parameters: %s", hipGetErrorString(e));
+        }
+        std::vector<float> host(dw_floats, 0.0f);
+        size_t off = 0;
+        std::vector<int32_t> ord;
+        for (int i = 0; i < n_items; ++i) {
+            sbn_chain::Item& it = c->items[(size_t)i];
+            if (it.item == SBN_ITEM_SPARSE) ord = it.packed->perm_out;
+            if (it.item != SBN_ITEM_DW3X3) continue;
+            const int ch_n = it.channels;
+            for (int ch = 0; ch < ch_n; ++ch) {
+                const int src = ord.empty() ? ch : ord[(size_t)ch];
+                for (int t = 0; t < 9; ++t) host[off + (size_t)t * ch_n + ch] = items[i].dw_w[(size_t)src * 9 + t];
+                host[off + (size_t)9 * ch_n + ch] = items[i].dw_bias ? items[i].dw_bias[src] : 0.0f;
+            }
+            it.d_w = blob + off;
+            it.d_b = blob + off + (size_t)9 * ch_n;
+            off += (size_t)10 * ch_n;
+        }
+        e = hipMemcpy(blob, host.data(), dw_floats * sizeof(float), hipMemcpyHostToDevice);
+        (void)hipSetDevice(prev);
+        if (e != hipSuccess) {
+            (void)hipFree(blob);
+            delete c;
+            return fail(SBN_EHIP, "chain parameters upload: %s", hipGetErrorString(e));
+        }
+        c->d_blob = blob;
+    }
+    *out = c;
+    return SBN_OK;
+}
+
+int sbn_chain_workspace(const sbn_chain_t* c, int n, int h, int w, size_t* bytes_out)
+{
+    clear_error();
+    if (!c || !bytes_out || n < 0 || h < 0 || w < 0) return fail(SBN_EINVAL, "sbn_chain_workspace: bad argument");
+    *bytes_out = 2 * max_intermediate(c, n, h, w);
+    return SBN_OK;
+}
+
+int sbn_chain_output_shape(const sbn_chain_t* c, int n, int h, int w, int* oh, int* ow, int* oc)
+{
+    clear_error();
+    if (!c || n < 0 || h < 0 || w < 0) return fail(SBN_EINVAL, "sbn_chain_output_shape: bad argument");
+    Shape s{n, h, w, c->c_in};
+    for (const auto& it : c->items) s = next_shape(it, s);
+    if (oh) *oh = s.h;
+    if (ow) *ow = s.w;
+    if (oc) *oc = s.c;
+    return SBN_OK;
+}
+
+int sbn_pointwise_chain(const sbn_chain_t* c, const float* x, float* y, int n, int h, int w, void* workspace,
+                        size_t workspace_bytes, float* const* layer_outputs, void* stream)
+{
+    clear_error();
+    if (!c) return fail(SBN_EINVAL, "sbn_pointwise_chain: chain is NULL");
+    if (n < 0 || h < 0 || w < 0) return fail(SBN_EINVAL, "sbn_pointwise_chain: negative extent");
+    if ((long long)n * h * w == 0) return SBN_OK;
+    if (!x || !y) return fail(SBN_EINVAL, "sbn_pointwise_chain: activation pointer is NULL");
+    const size_t half = max_intermediate(c, n, h, w);
+    if (c->items.size() > 1) {
+        if (!workspace || workspace_bytes < 2 * half)
+            return fail(SBN_EINVAL, "sbn_pointwise_chain: workspace of %zu bytes needed, %zu given", 2 * half, workspace_bytes);
+        if ((uintptr_t)workspace % 256) return fail(SBN_EINVAL, "sbn_pointwise_chain: workspace must be 256-byte aligned");
+    }
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return fail(SBN_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (cur != c->device) return fail(SBN_EINVAL, "sbn_pointwise_chain: current device is %d, chain lives on %d", cur, c->device);
+
+    float* buf[2] = {(float*)workspace, (float*)((char*)workspace + half)};
+    const float* src = x;
+    Shape s{n, h, w, c->c_in};
+    for (size_t i = 0; i < c->items.size(); ++i) {
+        const sbn_chain::Item& it = c->items[i];
+        const bool last = i + 1 == c->items.size();
+        float* dst = last ? y : buf[i & 1];
+        const Shape o = next_shape(it, s);
+        int rc = SBN_OK;
+        switch (it.item) {
+        case SBN_ITEM_SPARSE:
+            if (it.packed->kind == SBN_CONV1X1)
+                rc = launch_conv1x1(it.packed, src, dst, s.n * s.h * s.w, stream);
+            else
+                rc = launch_conv3x3(it.packed, src, dst, (int)s.n, s.h, s.w, stream);
+            break;
+        case SBN_ITEM_DW3X3:
+            rc = launch_dw3x3(src, dst, it.d_w, it.d_b, (int)s.n, s.h, s.w, s.c, it.stride, it.act, stream);
+            break;
+        case SBN_ITEM_AVGPOOL:
+            rc = launch_avgpool(src, dst, (int)s.n, s.h * s.w, s.c, stream);
+            break;
+        }
+        if (rc) return rc;
+        if (layer_outputs && layer_outputs[i]) {
+            if (o.bytes() % 16) return fail(SBN_EINVAL, "output of item %zu is not a multiple of 16 bytes", i);
+            rc = launch_copy(dst, layer_outputs[i], o.bytes(), stream);
+            if (rc) return rc;
+        }
+        src = dst;
+        s = o;
+    }
+    return SBN_OK;
+}
+
+void sbn_chain_free(sbn_chain_t* c)
+{
+    if (!c) return;
+    if (c->d_blob) (void)hipFree(c->d_blob);
+    delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,511 @@
+// Host side of libsbn: block importance, magnitude pruning, whole-network
+// rearrangement and the canonical group-sparse packer (offline steps of the
+// method: Section 3.2, Section 3.4, and the "sparse info" of Algorithm 1).
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+
+#include "sbn_internal.h"
+
+namespace sbn {
+
+static thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+void clear_error() { g_err.clear(); }
+
+bool is_permutation(const int32_t* p, int n)
+{
+    std::vector<char> seen((size_t)n, 0);
+    for (int i = 0; i < n; ++i) {
+        if (p[i] < 0 || p[i] >= n || seen[(size_t)p[i]]) return false;
+        seen[(size_t)p[i]] = 1;
+    }
+    return true;
+}
+
+// Section 3.2 / Eq. 2: importance of block (i, j) = l1 norm of the go x gi
+// (x kh x kw) weights it covers.  fp64, summed filter -> ky -> kx -> channel.
+void block_norms(const float* w, int c_out, int kh, int kw, int c_in, int go, int gi, std::vector<double>& out)
+{
+    const int rows = c_out / go, cols = c_in / gi;
+    out.assign((size_t)rows * cols, 0.0);
+    for (int i = 0; i < rows; ++i)
+        for (int j = 0; j < cols; ++j) {
+            double s = 0.0;
+            for (int o = 0; o < go; ++o)
+                for (int ky = 0; ky < kh; ++ky)
+                    for (int kx = 0; kx < kw; ++kx) {
+                        const float* q = w + ((((size_t)(i * go + o)) * kh + ky) * kw + kx) * c_in + (size_t)j * gi;
+                        for (int c = 0; c < gi; ++c) s += std::fabs((double)q[c]);
+                    }
+            out[(size_t)i * cols + j] = s;
+        }
+}
+
+static int check_geometry(int kind, int c_in, int c_out, int go, int gi)
+{
+    if (kind != SBN_CONV1X1 && kind != SBN_CONV3X3)
+        return fail(SBN_EINVAL, "kind must be SBN_CONV1X1 or SBN_CONV3X3 (got %d)", kind);
+    if (c_in <= 0 || c_out <= 0)
+        return fail(SBN_EINVAL, "c_in and c_out must be positive (got %d, %d)", c_in, c_out);
+    if (c_in > 65528) return fail(SBN_EINVAL, "c_in %d does not fit the 16-bit channel index", c_in);
+    if (go != 4 && go != 8) return fail(SBN_EINVAL, "go must be 4 or 8 (got %d)", go);
+    if (gi != 1 && gi != 2 && gi != 4 && gi != 8) return fail(SBN_EINVAL, "gi must be 1, 2, 4 or 8 (got %d)", gi);
+    if (c_out % go) return fail(SBN_ESHAPE, "c_out %d is not a multiple of go %d", c_out, go);
+    if (c_in % gi) return fail(SBN_ESHAPE, "c_in %d is not a multiple of gi %d", c_in, gi);
+    return SBN_OK;
+}
+
+static size_t removed_count(size_t n_blocks, int pct) { return n_blocks * (size_t)pct / 100; }
+
+// Permuted copy: wp[r][ky][kx][c] = w[perm_out[r]][ky][kx][perm_in[c]].
+static void permute_ohwi(const float* w, int c_out, int taps, int c_in, const int32_t* perm_out,
+                         const int32_t* perm_in, std::vector<float>& wp)
+{
+    wp.resize((size_t)c_out * taps * c_in);
+    for (int r = 0; r < c_out; ++r) {
+        const int ro = perm_out ? perm_out[r] : r;
+        for (int t = 0; t < taps; ++t) {
+            const float* src = w + ((size_t)ro * taps + t) * c_in;
+            float* dst = wp.data() + ((size_t)r * taps + t) * c_in;
+            if (perm_in)
+                for (int c = 0; c < c_in; ++c) dst[c] = src[perm_in[c]];
+            else
+                std::memcpy(dst, src, sizeof(float) * (size_t)c_in);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Rearrangement search (Section 3.4).  Works on per-filter column-group norms
+// a[f][j] = l1 norm of filter f over channel group j (all taps); the norm of a
+// block is the sum of a[f][j] over the go filters of its row group.
+// ---------------------------------------------------------------------------
+struct RowSearch {
+    int n = 0, go = 0, cols = 0, rows = 0;
+    size_t keep = 0;                       // number of blocks that survive pruning
+    std::vector<double> a;                 // [n][cols]
+    std::vector<int32_t> perm;             // current order, rows*go
+    std::vector<double> s;                 // block norms of the current order [rows][cols]
+    std::vector<double> tmp;
+
+    void row_norms(int row, const int32_t* members, double* out) const
+    {
+        (void)row;
+        for (int j = 0; j < cols; ++j) {
+            double v = 0.0;
+            for (int o = 0; o < go; ++o) v += a[(size_t)members[o] * cols + j];
+            out[j] = v;
+        }
+    }
+    void rebuild()
+    {
+        s.resize((size_t)rows * cols);
+        for (int i = 0; i < rows; ++i) row_norms(i, &perm[(size_t)i * go], &s[(size_t)i * cols]);
+    }
+    // sum of the `keep` largest entries of v (v is reordered)
+    double top_sum(std::vector<double>& v) const
+    {
+        if (keep == 0) return 0.0;
+        if (keep < v.size()) std::nth_element(v.begin(), v.begin() + (v.size() - keep), v.end());
+        double t = 0.0;
+        for (size_t i = v.size() - keep; i < v.size(); ++i) t += v[i];
+        return t;
+    }
+    double objective()
+    {
+        tmp = s;
+        return top_sum(tmp);
+    }
+};
+
+static inline uint64_t splitmix64(uint64_t& state)
+{
+    uint64_t z = (state += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+static void canonicalize(std::vector<int32_t>& perm, int go)
+{
+    const int rows = (int)perm.size() / go;
+    std::vector<std::vector<int32_t>> g((size_t)rows);
+    for (int i = 0; i < rows; ++i) {
+        g[(size_t)i].assign(perm.begin() + (size_t)i * go, perm.begin() + (size_t)(i + 1) * go);
+        std::sort(g[(size_t)i].begin(), g[(size_t)i].end());
+    }
+    std::sort(g.begin(), g.end(), [](const std::vector<int32_t>& x, const std::vector<int32_t>& y) { return x[0] < y[0]; });
+    for (int i = 0; i < rows; ++i) std::copy(g[(size_t)i].begin(), g[(size_t)i].end(), perm.begin() + (size_t)i * go);
+}
+
+// Enumerates every canonical grouping (first free filter opens a group, the
+// rest of the group is chosen in ascending combinations) and keeps the first
+// one with the largest objective.
+static void exhaustive(RowSearch& rs, std::vector<int32_t>& cur, std::vector<char>& used, int filled,
+                       double& best_obj, std::vector<int32_t>& best)
+{
+    const int n = rs.n, go = rs.go;
+    if (filled == n) {
+        rs.perm = cur;
+        rs.rebuild();
+        const double obj = rs.objective();
+        if (obj > best_obj) {
+            best_obj = obj;
+            best = cur;
+        }
+        return;
+    }
+    int first = 0;
+    while (used[(size_t)first]) ++first;
+    used[(size_t)first] = 1;
+    cur[(size_t)filled] = first;
+    // choose go-1 more members > first, ascending
+    std::vector<int> pick((size_t)go - 1);
+    std::vector<int> cand;
+    for (int f = first + 1; f < n; ++f)
+        if (!used[(size_t)f]) cand.push_back(f);
+    const int m = (int)cand.size(), k = go - 1;
+    if (k == 0) {
+        exhaustive(rs, cur, used, filled + 1, best_obj, best);
+    } else if (m >= k) {
+        std::vector<int> idx((size_t)k);
+        std::iota(idx.begin(), idx.end(), 0);
+        while (true) {
+            for (int t = 0; t < k; ++t) {
+                cur[(size_t)filled + 1 + t] = cand[(size_t)idx[(size_t)t]];
+                used[(size_t)cand[(size_t)idx[(size_t)t]]] = 1;
+            }
+            exhaustive(rs, cur, used, filled + go, best_obj, best);
+            for (int t = 0; t < k; ++t) used[(size_t)cand[(size_t)idx[(size_t)t]]] = 0;
+            int t = k - 1;
+            while (t >= 0 && idx[(size_t)t] == m - k + t) --t;
+            if (t < 0) break;
+            ++idx[(size_t)t];
+            for (int u = t + 1; u < k; ++u) idx[(size_t)u] = idx[(size_t)u - 1] + 1;
+        }
+    }
+    used[(size_t)first] = 0;
+}
+
+static void search_rows(const float* wc, int c_out, int taps, int c_in, int go, int gi, int pct, uint64_t seed,
+                        int max_iters, std::vector<int32_t>& perm_out)
+{
+    RowSearch rs;
+    rs.n = c_out;
+    rs.go = go;
+    rs.cols = c_in / gi;
+    rs.rows = c_out / go;
+    const size_t nb = (size_t)rs.rows * rs.cols;
+    rs.keep = nb - removed_count(nb, pct);
+    rs.a.assign((size_t)c_out * rs.cols, 0.0);
+    for (int f = 0; f < c_out; ++f)
+        for (int t = 0; t < taps; ++t) {
+            const float* q = wc + ((size_t)f * taps + t) * c_in;
+            for (int c = 0; c < c_in; ++c) rs.a[(size_t)f * rs.cols + c / gi] += std::fabs((double)q[c]);
+        }
+    perm_out.resize((size_t)c_out);
+    std::iota(perm_out.begin(), perm_out.end(), 0);
+
+    if (c_out <= 8) {
+        std::vector<int32_t> cur((size_t)c_out), best = perm_out;
+        std::vector<char> used((size_t)c_out, 0);
+        double best_obj = -1.0;
+        exhaustive(rs, cur, used, 0, best_obj, best);
+        perm_out = best;
+        return;
+    }
+
+    rs.perm = perm_out;
+    rs.rebuild();
+    double cur_obj = rs.objective();
+    if (rs.rows < 2) return;
+    uint64_t st = seed;
+    std::vector<double> ra((size_t)rs.cols), rb((size_t)rs.cols);
+    for (int it = 0; it < max_iters; ++it) {
+        const uint64_t r0 = splitmix64(st), r1 = splitmix64(st);
+        const int pa = (int)(r0 % (uint64_t)c_out);
+        int pb = (int)(r1 % (uint64_t)c_out);
+        const int ga = pa / go;
+        int gb = pb / go;
+        if (ga == gb) {                                   // force a different group, deterministically
+            gb = (gb + 1 + (int)((r1 >> 32) % (uint64_t)(rs.rows - 1))) % rs.rows;
+            pb = gb * go + pb % go;
+        }
+        std::swap(rs.perm[(size_t)pa], rs.perm[(size_t)pb]);
+        rs.row_norms(ga, &rs.perm[(size_t)ga * go], ra.data());
+        rs.row_norms(gb, &rs.perm[(size_t)gb * go], rb.data());
+        rs.tmp = rs.s;
+        std::copy(ra.begin(), ra.end(), rs.tmp.begin() + (size_t)ga * rs.cols);
+        std::copy(rb.begin(), rb.end(), rs.tmp.begin() + (size_t)gb * rs.cols);
+        const double obj = rs.top_sum(rs.tmp);
+        if (obj > cur_obj) {
+            cur_obj = obj;
+            std::copy(ra.begin(), ra.end(), rs.s.begin() + (size_t)ga * rs.cols);
+            std::copy(rb.begin(), rb.end(), rs.s.begin() + (size_t)gb * rs.cols);
+        } else {
+            std::swap(rs.perm[(size_t)pa], rs.perm[(size_t)pb]);
+        }
+    }
+    perm_out = rs.perm;
+    canonicalize(perm_out, go);
+}
+
+}  // namespace sbn
+
+using namespace sbn;
+
+extern "C" {
+
+const char* sbn_last_error(void) { return sbn::g_err.c_str(); }
+
+int sbn_prune_magnitude(const float* w, int kind, int c_in, int c_out, int go, int gi, int pct, uint8_t* mask_out)
+{
+    clear_error();
+    if (!w || !mask_out) return fail(SBN_EINVAL, "sbn_prune_magnitude: NULL pointer");
+    if (pct < 0 || pct > 100) return fail(SBN_EINVAL, "sparsity_percent must be in [0,100] (got %d)", pct);
+    if (int rc = check_geometry(kind, c_in, c_out, go, gi)) return rc;
+    const int k = kind == SBN_CONV3X3 ? 3 : 1;
+    std::vector<double> s;
+    block_norms(w, c_out, k, k, c_in, go, gi, s);
+    std::vector<uint32_t> order(s.size());
+    std::iota(order.begin(), order.end(), 0u);
+    std::sort(order.begin(), order.end(),
+              [&](uint32_t a, uint32_t b) { return s[a] < s[b] || (s[a] == s[b] && a < b); });
+    const size_t r = removed_count(s.size(), pct);
+    std::fill(mask_out, mask_out + s.size(), (uint8_t)1);
+    for (size_t i = 0; i < r; ++i) mask_out[order[i]] = 0;
+    return SBN_OK;
+}
+
+int sbn_retained_l1(const float* w, int kind, int c_in, int c_out, int go, int gi, int pct, double* out)
+{
+    clear_error();
+    if (!w || !out) return fail(SBN_EINVAL, "sbn_retained_l1: NULL pointer");
+    if (pct < 0 || pct > 100) return fail(SBN_EINVAL, "sparsity_percent must be in [0,100] (got %d)", pct);
+    if (int rc = check_geometry(kind, c_in, c_out, go, gi)) return rc;
+    const int k = kind == SBN_CONV3X3 ? 3 : 1;
+    std::vector<double> s;
+    block_norms(w, c_out, k, k, c_in, go, gi, s);
+    std::sort(s.begin(), s.end());
+    double t = 0.0;
+    for (size_t i = removed_count(s.size(), pct); i < s.size(); ++i) t += s[i];
+    *out = t;
+    return SBN_OK;
+}
+
+int sbn_rearrange(const sbn_layer_desc_t* layers, int n_layers, const int* parent, const int* keep_output_order,
+                  int pct, uint64_t seed, int max_iters, int32_t* const* perm_out)
+{
+    clear_error();
+    if (!layers || !parent || !perm_out || n_layers < 0) return fail(SBN_EINVAL, "sbn_rearrange: NULL pointer");
+    if (pct < 0 || pct > 100) return fail(SBN_EINVAL, "sparsity_percent must be in [0,100] (got %d)", pct);
+    if (max_iters < 0) return fail(SBN_EINVAL, "max_iters must be >= 0");
+    for (int l = 0; l < n_layers; ++l) {
+        const sbn_layer_desc_t& d = layers[l];
+        if (!d.w || !perm_out[l]) return fail(SBN_EINVAL, "sbn_rearrange: layer %d has a NULL pointer", l);
+        if (int rc = check_geometry(d.kind, d.c_in, d.c_out, d.go, d.gi)) return rc;
+        if (parent[l] >= l || parent[l] < -1)
+            return fail(SBN_ESHAPE, "parent[%d] = %d: parents must come first", l, parent[l]);
+        if (parent[l] >= 0 && layers[parent[l]].c_out != d.c_in)
+            return fail(SBN_ESHAPE, "layer %d reads %d channels but its parent %d writes %d", l, d.c_in, parent[l],
+                        layers[parent[l]].c_out);
+    }
+    std::vector<float> wc;
+    std::vector<int32_t> perm;
+    for (int l = 0; l < n_layers; ++l) {
+        const sbn_layer_desc_t& d = layers[l];
+        const int taps = d.kind == SBN_CONV3X3 ? 9 : 1;
+        if (keep_output_order && keep_output_order[l]) {
+            for (int i = 0; i < d.c_out; ++i) perm_out[l][i] = i;
+            continue;
+        }
+        const int32_t* pin = parent[l] >= 0 ? perm_out[parent[l]] : nullptr;
+        permute_ohwi(d.w, d.c_out, taps, d.c_in, nullptr, pin, wc);
+        uint64_t s = seed ^ (0xD1B54A32D192ED03ull * (uint64_t)(l + 1));
+        search_rows(wc.data(), d.c_out, taps, d.c_in, d.go, d.gi, pct, s, max_iters, perm);
+        std::copy(perm.begin(), perm.end(), perm_out[l]);
+    }
+    return SBN_OK;
+}
+
+int sbn_pack(const sbn_layer_desc_t* d, int device, sbn_packed_t** out)
+{
+    clear_error();
+    if (!d || !out) return fail(SBN_EINVAL, "sbn_pack: NULL pointer");
+    *out = nullptr;
+    if (!d->w) return fail(SBN_EINVAL, "sbn_pack: weights pointer is NULL");
+    if (int rc = check_geometry(d->kind, d->c_in, d->c_out, d->go, d->gi)) return rc;
+    if (d->act != SBN_ACT_NONE && d->act != SBN_ACT_RELU) return fail(SBN_EINVAL, "unknown activation %d", d->act);
+    if (d->kind == SBN_CONV1X1 && (d->stride != 1 || d->pad != 0))
+        return fail(SBN_EINVAL, "1x1 layers need stride 1, pad 0 (got %d, %d)", d->stride, d->pad);
+    if (d->kind == SBN_CONV3X3 && ((d->stride != 1 && d->stride != 2) || d->pad != 1))
+        return fail(SBN_EINVAL, "3x3 layers need stride 1 or 2 and pad 1 (got %d, %d)", d->stride, d->pad);
+    if (device < -1) return fail(SBN_EINVAL, "device must be >= -1");
+    if (d->perm_out && !is_permutation(d->perm_out, d->c_out)) return fail(SBN_EPERM, "perm_out is not a permutation of 0..%d", d->c_out - 1);
+    if (d->perm_in && !is_permutation(d->perm_in, d->c_in)) return fail(SBN_EPERM, "perm_in is not a permutation of 0..%d", d->c_in - 1);
+
+    sbn_packed* p = new (std::nothrow) sbn_packed;
+    if (!p) return fail(SBN_ENOMEM, "out of host memory");
+    try {
+        p->kind = d->kind;
+        p->c_in = d->c_in;
+        p->c_out = d->c_out;
+        p->go = d->go;
+        p->gi = d->gi;
+        p->stride = d->stride;
+        p->pad = d->pad;
+        p->act = d->act;
+        p->kh = p->kw = d->kind == SBN_CONV3X3 ? 3 : 1;
+        p->device = device;
+        const int taps = p->kh * p->kw, go = d->go, gi = d->gi;
+        const int rows = d->c_out / go, cols = d->c_in / gi;
+
+        p->perm_out.resize((size_t)d->c_out);
+        p->perm_in.resize((size_t)d->c_in);
+        for (int i = 0; i < d->c_out; ++i) p->perm_out[(size_t)i] = d->perm_out ? d->perm_out[i] : i;
+        for (int i = 0; i < d->c_in; ++i) p->perm_in[(size_t)i] = d->perm_in ? d->perm_in[i] : i;
+        p->has_bias = d->bias != nullptr;
+        p->bias.assign((size_t)d->c_out, 0.0f);
+        if (d->bias)
+            for (int i = 0; i < d->c_out; ++i) p->bias[(size_t)i] = d->bias[p->perm_out[(size_t)i]];
+
+        std::vector<float> wp;
+        permute_ohwi(d->w, d->c_out, taps, d->c_in, d->perm_out, d->perm_in, wp);
+
+        // Gather kept blocks row by row, ascending channel inside a row.
+        p->row_ptr.assign((size_t)rows + 1, 0u);
+        const size_t blk = (size_t)taps * gi * go;
+        for (int i = 0; i < rows; ++i) {
+            for (int j = 0; j < cols; ++j) {
+                bool kept;
+                if (d->mask) {
+                    kept = d->mask[(size_t)i * cols + j] != 0;
+                } else {
+                    kept = false;
+                    for (int o = 0; o < go && !kept; ++o)
+                        for (int t = 0; t < taps && !kept; ++t) {
+                            const float* q = wp.data() + ((size_t)(i * go + o) * taps + t) * d->c_in + (size_t)j * gi;
+                            for (int c = 0; c < gi; ++c) {
+                                uint32_t bits;
+                                std::memcpy(&bits, q + c, 4);
+                                if (bits & 0x7FFFFFFFu) {
+                                    kept = true;
+                                    break;
+                                }
+                            }
+                        }
+                }
+                if (!kept) continue;
+                p->kidx.push_back((uint16_t)(j * gi));
+                const size_t base = p->vals.size();
+                p->vals.resize(base + blk);
+                for (int t = 0; t < taps; ++t)
+                    for (int c = 0; c < gi; ++c)
+                        for (int o = 0; o < go; ++o)
+                            p->vals[base + ((size_t)t * gi + c) * go + o] =
+                                wp[((size_t)(i * go + o) * taps + t) * d->c_in + (size_t)j * gi + c];
+            }
+            p->row_ptr[(size_t)i + 1] = (uint32_t)p->kidx.size();
+        }
+        build_device_layout(p);
+    } catch (const std::bad_alloc&) {
+        delete p;
+        return fail(SBN_ENOMEM, "out of host memory while packing");
+    }
+    if (device >= 0) {
+        if (int rc = upload_device_layout(p)) {
+            delete p;
+            return rc;
+        }
+    }
+    *out = p;
+    return SBN_OK;
+}
+
+int sbn_unpack(const sbn_packed_t* p, float* w_out, uint8_t* mask_out)
+{
+    clear_error();
+    if (!p || !w_out) return fail(SBN_EINVAL, "sbn_unpack: NULL pointer");
+    const int taps = p->kh * p->kw, go = p->go, gi = p->gi;
+    const int rows = p->c_out / go, cols = p->c_in / gi;
+    std::fill(w_out, w_out + (size_t)p->c_out * taps * p->c_in, 0.0f);
+    if (mask_out) std::fill(mask_out, mask_out + (size_t)rows * cols, (uint8_t)0);
+    const size_t blk = (size_t)taps * gi * go;
+    for (int i = 0; i < rows; ++i)
+        for (uint32_t e = p->row_ptr[(size_t)i]; e < p->row_ptr[(size_t)i + 1]; ++e) {
+            const int k0 = p->kidx[e];
+            if (mask_out) mask_out[(size_t)i * cols + k0 / gi] = 1;
+            for (int t = 0; t < taps; ++t)
+                for (int c = 0; c < gi; ++c)
+                    for (int o = 0; o < go; ++o) {
+                        const int fo = p->perm_out[(size_t)(i * go + o)];
+                        const int co = p->perm_in[(size_t)(k0 + c)];
+                        w_out[((size_t)fo * taps + t) * p->c_in + co] = p->vals[e * blk + ((size_t)t * gi + c) * go + o];
+                    }
+        }
+    return SBN_OK;
+}
+
+int sbn_export(const sbn_packed_t* p, uint32_t* row_ptr, uint16_t* kidx, float* vals, int32_t* perm_out,
+               int32_t* perm_in, float* bias, size_t* nnz_out)
+{
+    clear_error();
+    if (!p) return fail(SBN_EINVAL, "sbn_export: NULL pointer");
+    if (row_ptr) std::copy(p->row_ptr.begin(), p->row_ptr.end(), row_ptr);
+    if (kidx) std::copy(p->kidx.begin(), p->kidx.end(), kidx);
+    if (vals) std::copy(p->vals.begin(), p->vals.end(), vals);
+    if (perm_out) std::copy(p->perm_out.begin(), p->perm_out.end(), perm_out);
+    if (perm_in) std::copy(p->perm_in.begin(), p->perm_in.end(), perm_in);
+    if (bias) std::copy(p->bias.begin(), p->bias.end(), bias);
+    if (nnz_out) *nnz_out = p->kidx.size();
+    return SBN_OK;
+}
+
+int sbn_packed_info(const sbn_packed_t* p, int* kind, int* c_in, int* c_out, int* go, int* gi, int* stride, int* act,
+                    int* device)
+{
+    clear_error();
+    if (!p) return fail(SBN_EINVAL, "sbn_packed_info: NULL pointer");
+    if (kind) *kind = p->kind;
+    if (c_in) *c_in = p->c_in;
+    if (c_out) *c_out = p->c_out;
+    if (go) *go = p->go;
+    if (gi) *gi = p->gi;
+    if (stride) *stride = p->stride;
+    if (act) *act = p->act;
+    if (device) *device = p->device;
+    return SBN_OK;
+}
+
+int sbn_packed_work(const sbn_packed_t* p, size_t* nnz, size_t* macs)
+{
+    clear_error();
+    if (!p) return fail(SBN_EINVAL, "sbn_packed_work: NULL pointer");
+    if (nnz) *nnz = p->kidx.size();
+    if (macs) *macs = p->kidx.size() * (size_t)p->go * p->gi * p->kh * p->kw;
+    return SBN_OK;
+}
+
+void sbn_free(sbn_packed_t* p)
+{
+    if (!p) return;
+    release_device_layout(p);
+    delete p;
+}
+
+}  // extern "C"

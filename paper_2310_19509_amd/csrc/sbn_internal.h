@@ -1,0 +1,89 @@
+// Internal declarations shared by the host runtime and the kernel launchers of
+// libsbn.  Nothing here is part of the public ABI (see include/sbn.h).
+#pragma once
+
+#include <cstdarg>
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "sbn.h"
+
+namespace sbn {
+
+// ---- error reporting -------------------------------------------------------
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+// ---- device-side layout ----------------------------------------------------
+// The canonical rows (one per output group of `go` filters) are regrouped for
+// the kernels into BUNDLES of kBundleGroups consecutive groups of 4 filters.
+// A bundle walks the union of its groups' kept 4-channel pieces in ascending
+// channel order; an ENTRY is one such piece:
+//     entry = (kb4 << 8) | present_mask        kb4 = first channel / 4
+// bit g of present_mask says that group g of the bundle keeps the piece.  The
+// weights of an entry are stored for all groups of the bundle (zeros where
+// absent) so that one 64-lane load yields [g][ci][co] for every group:
+//     1x1:  wts[entry][g][ci][co]                 64 floats per entry
+//     3x3:  wts[entry][tap][g][ci][co]            9*64 floats per entry
+// chunk_ptr32[bundle][c] is the first entry of the bundle whose channel is
+// >= 32*c (c = 0 .. ceil(c_in/32)), as a global entry index.
+constexpr int kBundleGroups = 4;                       // groups of 4 filters per bundle
+constexpr int kBundleChannels = 4 * kBundleGroups;     // 16 output channels per bundle
+
+struct DeviceLayout {
+    int n_bundles = 0;
+    int n_chunks32 = 0;
+    size_t n_entries = 0;
+    // host staging (kept so that sbn_free needs no device reads; small)
+    std::vector<uint32_t> entries;
+    std::vector<float> wts;
+    std::vector<uint32_t> chunk_ptr32;
+    std::vector<float> bias_padded;       // [n_bundles * 16], zeros when no bias
+    // device copies (one allocation)
+    void* d_blob = nullptr;
+    uint32_t* d_entries = nullptr;
+    float* d_wts = nullptr;
+    uint32_t* d_chunk_ptr32 = nullptr;
+    float* d_bias = nullptr;
+};
+
+}  // namespace sbn
+
+struct sbn_packed {
+    int kind = 0, c_in = 0, c_out = 0, go = 0, gi = 0, stride = 1, pad = 0, act = 0;
+    int kh = 1, kw = 1;
+    int device = -1;
+    bool has_bias = false;
+    // canonical format
+    std::vector<uint32_t> row_ptr;    // [c_out/go + 1]
+    std::vector<uint16_t> kidx;       // [nnz]
+    std::vector<float> vals;          // [nnz][kh][kw][gi][go]
+    std::vector<int32_t> perm_out;    // [c_out]
+    std::vector<int32_t> perm_in;     // [c_in]
+    std::vector<float> bias;          // [c_out] packed order (zeros if !has_bias)
+    sbn::DeviceLayout dev;
+};
+
+namespace sbn {
+
+// Builds p->dev host arrays from the canonical arrays (no HIP calls).
+void build_device_layout(sbn_packed* p);
+// Uploads p->dev to p->device.  Returns SBN_OK or an error code.
+int upload_device_layout(sbn_packed* p);
+void release_device_layout(sbn_packed* p);
+
+// Kernel launchers (defined in the .hip files).
+int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long m, void* stream);
+int launch_conv3x3(const sbn_packed* p, const float* x, float* y, int n, int h, int w, void* stream);
+int launch_dw3x3(const float* x, float* y, const float* w_dev, const float* b_dev, int n, int h, int w,
+                 int c, int stride, int act, void* stream);
+int launch_avgpool(const float* x, float* y, int n, int hw, int c, void* stream);
+int launch_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+// Block l1 norms in the exact summation order the pruning rule is defined with.
+void block_norms(const float* w, int c_out, int kh, int kw, int c_in, int go, int gi, std::vector<double>& out);
+bool is_permutation(const int32_t* p, int n);
+
+}  // namespace sbn

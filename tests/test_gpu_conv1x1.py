@@ -1,0 +1,143 @@
+"""Parity of the HIP group-sparse 1x1 convolution with the CPU oracle (gpu)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2310_19509_amd as S
+from oracle import reference as R
+import workloads as W
+from helpers import assert_within_bound
+
+pytestmark = pytest.mark.gpu
+
+
+def run_layer(x, w, go, gi, mask=None, bias=None, perm_out=None, perm_in=None, act=S.SBN_ACT_NONE, pct=None):
+    """x: NHWC numpy in PERMUTED channel order.  Returns (y_gpu, y_ref, bound)."""
+    if pct is not None:
+        mask = S.sbn_prune_magnitude(R.permute_weights(w, perm_out, perm_in), S.SBN_CONV1X1, go, gi, pct)
+        assert np.array_equal(mask, R.prune_mask(R.permute_weights(w, perm_out, perm_in), go, gi, pct))
+    p = S.sbn_pack(S.SBN_CONV1X1, w, go, gi, mask=mask, bias=bias, perm_out=perm_out, perm_in=perm_in, act=act)
+    n, h, ww, _ = x.shape
+    xd = torch.from_numpy(x).cuda()
+    yd = torch.full((n, h, ww, w.shape[0]), float("nan"), device="cuda", dtype=torch.float32)
+    S.sbn_conv1x1_sparse(p, xd, yd, n, h, ww)
+    torch.cuda.synchronize()
+    y_ref, bound = R.sparse_conv_reference(x, w, mask, go, gi, bias=bias, perm_out=perm_out, perm_in=perm_in, act=act)
+    return yd.cpu().numpy(), y_ref, bound
+
+
+def test_config1():
+    c = W.config1()
+    y, ref, bound = run_layer(c["x"], c["w"], 4, 4, mask=c["mask"])
+    assert_within_bound(y, ref, bound, "config1")
+
+
+CASES = [
+    # n, h, w, K, N, go, gi, pct, bias, relu, perms
+    (1, 1, 1, 8, 8, 4, 4, 50, True, False, False),          # one pixel
+    (1, 7, 7, 32, 64, 4, 4, 90, True, True, False),         # M=49, empty rows
+    (1, 14, 14, 64, 128, 4, 4, 0, False, False, False),     # M=196, all kept
+    (1, 14, 14, 64, 128, 8, 4, 50, True, True, True),       # go=8
+    (2, 5, 5, 64, 32, 4, 1, 50, True, False, True),         # gi=1
+    (2, 5, 5, 64, 32, 4, 2, 70, True, False, False),        # gi=2
+    (2, 5, 5, 64, 32, 8, 8, 30, False, True, True),         # gi=8
+    (1, 3, 3, 24, 24, 4, 4, 30, True, False, True),         # K, N not multiples of 32 / 16
+    (1, 3, 3, 40, 72, 8, 4, 50, True, True, False),         # K=40, N=72
+    (1, 3, 3, 6, 12, 4, 2, 30, True, False, False),         # K not a multiple of 4 (scalar staging)
+    (1, 3, 3, 70, 12, 4, 1, 50, True, False, True),         # K=70, two chunks, scalar staging
+    (1, 7, 7, 1024, 1024, 4, 4, 30, True, True, False),     # widest layer
+    (1, 7, 7, 512, 1024, 8, 4, 70, True, False, False),
+    (3, 9, 11, 128, 256, 4, 4, 30, True, True, True),       # M=297: several tiles + ragged tail
+    (1, 2, 2, 32, 16, 4, 4, 100, True, True, False),        # everything pruned
+]
+
+
+@pytest.mark.parametrize("n,h,w,K,N,go,gi,pct,use_bias,relu,perms", CASES)
+def test_shapes(n, h, w, K, N, go, gi, pct, use_bias, relu, perms):
+    seed = 7000 + K + N + go + gi + pct
+    wt = W.he_weights(seed, N, 1, 1, K)
+    b = W.small_bias(seed + 1, N) * 20 if use_bias else None
+    x = W.uniform_activation(seed + 2, (n, h, w, K))
+    po = W.random_permutation(seed + 3, N) if perms else None
+    pi = W.random_permutation(seed + 4, K) if perms else None
+    y, ref, bound = run_layer(x, wt, go, gi, bias=b, perm_out=po, perm_in=pi,
+                              act=S.SBN_ACT_RELU if relu else S.SBN_ACT_NONE, pct=pct)
+    assert_within_bound(y, ref, bound, f"case {n,h,w,K,N,go,gi,pct}")
+    if pct == 100:
+        expect = np.zeros(N, np.float32) if b is None else (b if po is None else b[po])
+        if relu:
+            expect = np.maximum(expect, 0)
+        assert np.array_equal(y, np.broadcast_to(expect, y.shape))
+
+
+def test_uneven_rows_from_hand_mask():
+    """One row keeps every block, one keeps none, others one block each."""
+    K, N = 64, 32
+    w = W.he_weights(7101, N, 1, 1, K)
+    mask = np.zeros((N // 4, K // 4), dtype=np.uint8)
+    mask[0, :] = 1
+    for i in range(2, 8):
+        mask[i, (5 * i) % 16] = 1
+    x = W.uniform_activation(7102, (1, 9, 9, K))
+    y, ref, bound = run_layer(x, w, 4, 4, mask=mask, bias=W.small_bias(7103, N))
+    assert_within_bound(y, ref, bound, "hand mask")
+
+
+def test_large_m_uses_two_pixel_sets_per_wave():
+    """Enough pixels for the 128-pixel-per-workgroup variant, with a ragged tail."""
+    K, N = 32, 64
+    m = 1024 * 128 + 77
+    w = W.he_weights(7201, N, 1, 1, K)
+    x = W.uniform_activation(7202, (1, 1, m, K))
+    y, ref, bound = run_layer(x, w, 4, 4, bias=W.small_bias(7203, N), act=S.SBN_ACT_RELU, pct=50)
+    assert_within_bound(y, ref, bound, "large M")
+
+
+def test_zero_pixels_and_argument_errors():
+    c = W.config1()
+    p = S.sbn_pack(S.SBN_CONV1X1, c["w"], 4, 4, mask=c["mask"])
+    x = torch.zeros(4, 64, device="cuda")
+    y = torch.zeros(4, 128, device="cuda")
+    S.sbn_conv1x1_sparse(p, x, y, 0, 14, 14)          # nothing to do
+    with pytest.raises(S.SbnError):
+        S.sbn_conv1x1_sparse(p, x, x, 1, 2, 2)        # aliasing
+    with pytest.raises(S.SbnError):
+        S.sbn_conv3x3_sparse(p, x, y, 1, 2, 2)        # wrong kind
+    with pytest.raises(S.SbnError):
+        S.sbn_conv1x1_sparse(p, x, y, -1, 2, 2)
+
+
+def test_nonblocking_stream():
+    c = W.config1()
+    p = S.sbn_pack(S.SBN_CONV1X1, c["w"], 4, 4, mask=c["mask"])
+    st = torch.cuda.Stream()
+    xd = torch.from_numpy(c["x"]).cuda()
+    yd = torch.empty(1, 14, 14, 128, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        S.sbn_conv1x1_sparse(p, xd, yd, 1, 14, 14)
+    st.synchronize()
+    ref, bound = R.sparse_conv_reference(c["x"], c["w"], c["mask"], 4, 4)
+    assert_within_bound(yd.cpu().numpy(), ref, bound, "side stream")
+
+
+@pytest.mark.parametrize("layer_idx,pct,go", [(1, 30, 4), (3, 50, 4), (7, 30, 4), (7, 70, 8), (13, 30, 4), (13, 90, 8)])
+def test_full_size_batch64_sampled(layer_idx, pct, go):
+    """MobileNet-v1 pointwise layers at batch 64: every output of 4096 sampled pixels."""
+    L = W.MOBILENET_V1_PW[layer_idx - 1]
+    t = W.pw_layer_tensors(3000, L, 64, with_x=False)
+    m = 64 * L.hw * L.hw
+    g = torch.Generator(device="cuda").manual_seed(3000 + layer_idx)
+    xd = torch.rand((m, L.c_in), device="cuda", generator=g) * 2 - 1
+    mask = S.sbn_prune_magnitude(t["w"], S.SBN_CONV1X1, go, 4, pct)
+    p = S.sbn_pack(S.SBN_CONV1X1, t["w"], go, 4, mask=mask, bias=t["bias"], act=S.SBN_ACT_RELU)
+    yd = torch.full((m, L.c_out), float("nan"), device="cuda")
+    S.sbn_conv1x1_sparse(p, xd, yd, 64, L.hw, L.hw)
+    torch.cuda.synchronize()
+    assert torch.isfinite(yd).all()
+    rng = np.random.default_rng(layer_idx)
+    idx = np.unique(np.concatenate([rng.integers(0, m, 4000), np.arange(0, 64), np.arange(m - 64, m)]))
+    xs = xd[torch.from_numpy(idx).cuda()].cpu().numpy()
+    ys = yd[torch.from_numpy(idx).cuda()].cpu().numpy()
+    ref, bound = R.sparse_conv_reference(xs[None, None], t["w"], mask, go, 4, bias=t["bias"], act=S.SBN_ACT_RELU)
+    assert_within_bound(ys[None, None], ref, bound, f"pw{layer_idx} rho={pct} go={go}")
