@@ -3,26 +3,48 @@
 // Mapping.  One lane owns one pixel (a wave owns 64*P pixels); a wave owns one
 // bundle of four 4-filter output groups, a workgroup of four waves owns four
 // bundles (64 output channels) over the same pixels.  The activation tile
-// X[64*P pixels][KC channels] is staged once per workgroup in LDS, row stride
-// KC+4 floats so that the per-lane 16-byte row reads are bank-conflict free.
+// X[64*P pixels][64 channels] is staged once per workgroup and chunk in LDS,
+// row stride 68 floats so that per-lane 16-byte row accesses are conflict free.
 //
 // Inner step (one ENTRY = one 4-channel piece kept by at least one group of
-// the bundle): each lane reads its pixel's 4 channels from LDS (one
-// ds_read_b128 per pixel set), the wave loads the 64 weights of the entry
-// ([group][ci][co], one float per lane), and for every group whose bit is
-// set issues 4 x v_mfma_f32_4x4x1 (16 blocks): block b multiplies the weight
-// column w[ci][0..3] -- broadcast from lanes 4*abid..4*abid+3 of the weight
-// register to all 16 blocks -- with the activations of pixels 4b..4b+3.  The
-// accumulator register i of lane L then holds output channel i of pixel L.
-// The staged activation is reused by every group of the bundle that keeps the
-// piece; the weight register is reused by every pixel set.
+// the bundle): each lane reads its pixel's 4 channels from LDS (ds_read_b128
+// per pixel set) and, for every group whose bit is set, the wave issues
+// 4*P v_mfma_f32_4x4x1 (16 blocks each): block b multiplies the weight column
+// w[co 0..3][ci] -- broadcast from lanes 4*abid..4*abid+3 of a weight register
+// to all 16 blocks -- with the activations of pixels 4b..4b+3, so accumulator
+// register i of lane L holds output channel i of pixel L.  The staged
+// activation is reused by every group of the bundle that keeps the piece, a
+// weight register by every pixel set.  The weights of a whole 64-channel chunk
+// (at most 16 entries = 4 x 16-byte loads per lane) are fetched one chunk
+// ahead, together with the next activation chunk, while the current chunk is
+// being multiplied.  Dependent MFMAs stall the matrix pipe, so every (pixel
+// set, group) pair accumulates into 4/P interleaved partial sums.
+//
+// Epilogue: partial sums are added, bias and activation applied, the 64*P x 64
+// output tile is transposed through LDS and written with full-row 16-byte
+// stores (a wave instruction covers whole 256-byte rows).
 #include <hip/hip_runtime.h>
 
 #include "sbn_internal.h"
 
+#ifdef SBN_TRACE
+__device__ unsigned long long sbn_trace_buf[8 * 4 * 128];
+extern "C" int sbn_trace_read(unsigned long long* out)
+{
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sbn_trace_buf), sizeof(unsigned long long) * 8 * 4 * 128);
+}
+#define SBN_TS(i)                                                                                         \
+    if (lane == 0 && (blockIdx.x % 200) == 0 && blockIdx.x / 200 < 8)                                      \
+        sbn_trace_buf[((blockIdx.x / 200) * 4 + wave) * 128 + (i)] = __builtin_readcyclecounter();
+#else
+#define SBN_TS(i)
+#endif
+
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int S = 68;      // LDS row stride in floats (64 + 4 padding)
 
 template <int ABID>
 __device__ __forceinline__ v4f mfma_bcast(float w, float x, v4f c)
@@ -31,48 +53,63 @@ __device__ __forceinline__ v4f mfma_bcast(float w, float x, v4f c)
     return __builtin_amdgcn_mfma_f32_4x4x1f32(w, x, c, 4, ABID, 0);
 }
 
-template <int P>
-struct Stage {
-    float wv;
-    v4f xv[P];
-};
-
-template <int P, int G>
-__device__ __forceinline__ void group_fma(const Stage<P>& s, v4f (&acc)[P][4])
+// acc[p][g][a]: pixel set p, group g, partial sum a (input channel ci goes to a = ci % NA)
+template <int P, int NA, int Q4, int G>
+__device__ __forceinline__ void group_fma(const v4f& w, const v4f (&xv)[P], v4f (&acc)[P][4][NA])
 {
 #pragma unroll
-    for (int p = 0; p < P; ++p) acc[p][G] = mfma_bcast<4 * G + 0>(s.wv, s.xv[p].x, acc[p][G]);
+    for (int p = 0; p < P; ++p) acc[p][G][0 % NA] = mfma_bcast<Q4 * 4 + G>(w.x, xv[p].x, acc[p][G][0 % NA]);
 #pragma unroll
-    for (int p = 0; p < P; ++p) acc[p][G] = mfma_bcast<4 * G + 1>(s.wv, s.xv[p].y, acc[p][G]);
+    for (int p = 0; p < P; ++p) acc[p][G][1 % NA] = mfma_bcast<Q4 * 4 + G>(w.y, xv[p].y, acc[p][G][1 % NA]);
 #pragma unroll
-    for (int p = 0; p < P; ++p) acc[p][G] = mfma_bcast<4 * G + 2>(s.wv, s.xv[p].z, acc[p][G]);
+    for (int p = 0; p < P; ++p) acc[p][G][2 % NA] = mfma_bcast<Q4 * 4 + G>(w.z, xv[p].z, acc[p][G][2 % NA]);
 #pragma unroll
-    for (int p = 0; p < P; ++p) acc[p][G] = mfma_bcast<4 * G + 3>(s.wv, s.xv[p].w, acc[p][G]);
+    for (int p = 0; p < P; ++p) acc[p][G][3 % NA] = mfma_bcast<Q4 * 4 + G>(w.w, xv[p].w, acc[p][G][3 % NA]);
 }
 
-// P: pixel sets of 64 per wave.  KC: channels per LDS chunk (32 or 64).
-// VEC: c_in % 4 == 0 (16-byte activation loads); otherwise scalar loads.
-template <int P, int KC, bool VEC>
-__global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ x, float* __restrict__ y,
-                                                      const uint32_t* __restrict__ entries,
-                                                      const float* __restrict__ wts,
-                                                      const uint32_t* __restrict__ chunk_ptr32,
-                                                      const float* __restrict__ bias, long long M, int K, int N,
-                                                      int n_bundles, int n_chunks32, int n_col_tiles,
-                                                      int n_pix_tiles, int act)
+template <int P, int NA, int Q4>
+__device__ __forceinline__ void entry_fma(uint32_t m, const v4f& w, const v4f (&xv)[P], v4f (&acc)[P][4][NA])
 {
-    constexpr int T = 64 * P;          // pixels per workgroup
-    constexpr int S = KC + 4;          // LDS row stride in floats
-    constexpr int C4 = KC / 4;         // float4 slots per row
-    __shared__ __attribute__((aligned(16))) float lds[T * S];
+    // a taken branch costs the wave tens of cycles: keep "present" the fall-through path
+    if (__builtin_expect((m & 1u) != 0, 1)) group_fma<P, NA, Q4, 0>(w, xv, acc);
+    if (__builtin_expect((m & 2u) != 0, 1)) group_fma<P, NA, Q4, 1>(w, xv, acc);
+    if (__builtin_expect((m & 4u) != 0, 1)) group_fma<P, NA, Q4, 2>(w, xv, acc);
+    if (__builtin_expect((m & 8u) != 0, 1)) group_fma<P, NA, Q4, 3>(w, xv, acc);
+}
+
+struct Record {
+    uint32_t d[16];
+};
+
+// P: pixel sets of 64 per wave.  NA: partial sums per (pixel set, group).
+// RS: 16-byte slots per staged LDS row, 17 (64 channels + pad) or 9 (32 + pad,
+// for layers with c_in <= 32).  VEC: c_in % 4 == 0, activations go from global
+// memory straight into LDS (global_load_lds_dwordx4); otherwise they are staged
+// through registers with scalar loads.
+template <int P, int NA, int RS, bool VEC>
+__global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                      const uint32_t* __restrict__ records,
+                                                      const uint32_t* __restrict__ woff,
+                                                      const float* __restrict__ wts, const float* __restrict__ bias,
+                                                      long long M, int K, int N, int n_bundles, int n_chunks,
+                                                      int n_col_tiles, int n_pix_tiles, int act)
+{
+    constexpr int T = 64 * P;                  // pixels per workgroup
+    constexpr int KC = (RS - 1) * 4;           // channels staged per chunk
+    constexpr int XS = RS * 4;                 // staged row stride in floats
+    constexpr int XBUF = T * XS;               // floats per activation buffer
+    constexpr int OBUF = T * S;                // floats of the output tile
+    constexpr bool DB = VEC && RS == 17;       // two activation buffers (multi-chunk layers)
+    constexpr int LDS_FLOATS = (DB ? 2 * XBUF : XBUF) > OBUF ? (DB ? 2 * XBUF : XBUF) : OBUF;
+    __shared__ __attribute__((aligned(16))) float lds[LDS_FLOATS];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     // Workgroup -> (pixel tile, column tile).  Consecutive workgroup ids go to
     // different XCDs (8 of them, each with its own L2); the column tiles of
-    // one pixel tile are given ids that differ by multiples of 8 so that they
-    // run on the same XCD and share the activation tile in its L2.
+    // one pixel tile get ids that differ by multiples of 8 so that they run on
+    // the same XCD and share the activation tile in its L2.
     const int id = blockIdx.x;
     const int xcd = id & 7, j = id >> 3;
     const int pix_tile = (j / n_col_tiles) * 8 + xcd;
@@ -81,133 +118,200 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
     const long long pix0 = (long long)pix_tile * T;
     const int bundle = col_tile * 4 + wave;
     const bool active = bundle < n_bundles;
+    const int bsafe = active ? bundle : 0;
 
-    v4f acc[P][4];
+    v4f acc[P][4][NA];
 #pragma unroll
     for (int p = 0; p < P; ++p)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) acc[p][g] = (v4f){0.f, 0.f, 0.f, 0.f};
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int a = 0; a < NA; ++a) acc[p][g][a] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    const uint32_t* cp = chunk_ptr32 + (size_t)(active ? bundle : 0) * (n_chunks32 + 1);
-    const char* lds_lane = (const char*)lds + lane * (S * 4);
-    const int n_chunks = (K + KC - 1) / KC;
-
-    // Global -> register loads of one chunk (issued together so that their
-    // latencies overlap), then register -> LDS.  Rows past the last pixel and
-    // channels past c_in are staged as zeros.
+    // ---- activation staging -------------------------------------------------
+    // VEC: a wave instruction moves 64 x 16 bytes from global memory to 1024
+    // contiguous LDS bytes.  The tile is T rows of RS slots (the last slot of a
+    // row is padding); slot g = row * RS + col.  Wave w issues instructions
+    // w, w+4, ... of the tile's T*RS/64.  Padding slots, rows past the last
+    // pixel and channels past c_in fetch some valid address instead: no entry
+    // ever reads those channels and a lane only ever reads its own pixel's row.
+    constexpr int NI = (T * RS / 64 + 3) / 4;          // instructions per wave
+    const float* grow[VEC ? NI : 1];           // first channel of the slot's pixel
+    int gcol[VEC ? NI : 1];                    // channel offset of the slot inside a chunk
+    if (VEC) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int g = ((i * 4 + wave) * 64 + lane) % (T * RS);
+            const int row = g / RS, col = g % RS;
+            long long pix = pix0 + row;
+            pix = pix < M ? pix : M - 1;
+            grow[i] = x + pix * K;
+            gcol[i] = (col < RS - 1 ? col : RS - 2) * 4;
+        }
+    }
+    auto issue_x_direct = [&](int c, float* buf) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            if ((i * 4 + wave) * 64 < T * RS) {
+                const int ch = min(c * KC + gcol[i], K - 4);      // keep the 16-byte read inside the row
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(grow[i] + ch),
+                                                 (__attribute__((address_space(3))) void*)(buf + (i * 4 + wave) * 256),
+                                                 16, 0, 0);
+            }
+        }
+    };
+    // !VEC: registers, scalar loads, zero fill.
+    constexpr int C4 = KC / 4;
     constexpr int NL = T * C4 / 256;
-    v4f stage_reg[NL];
-    auto issue_loads = [&](int c) {
-        const int ch0 = c * KC;
+    v4f stage_reg[VEC ? 1 : NL];
+    auto issue_x_regs = [&](int c) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int slot = i * 256 + threadIdx.x;
             const int row = slot / C4, col = (slot % C4) * 4;
             const long long pix = pix0 + row;
             const long long pixc = pix < M ? pix : M - 1;
-            if (VEC) {
-                const int chc = ch0 + col < K ? ch0 + col : 0;
-                const v4f v = *(const v4f*)(x + pixc * K + chc);
-                const bool ok = pix < M && ch0 + col < K;
-                stage_reg[i] = ok ? v : (v4f){0.f, 0.f, 0.f, 0.f};
-            } else {
-                v4f v;
-                for (int q = 0; q < 4; ++q) {
-                    const int ch = ch0 + col + q;
-                    const float t = x[pixc * K + (ch < K ? ch : 0)];
-                    v[q] = (pix < M && ch < K) ? t : 0.f;
-                }
-                stage_reg[i] = v;
+            v4f v;
+            for (int q = 0; q < 4; ++q) {
+                const int ch = c * KC + col + q;
+                const float t = x[pixc * K + (ch < K ? ch : 0)];
+                v[q] = (pix < M && ch < K) ? t : 0.f;
             }
+            stage_reg[i] = v;
         }
     };
-    auto write_lds = [&]() {
+    auto write_x_regs = [&](float* buf) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int slot = i * 256 + threadIdx.x;
             const int row = slot / C4, col = (slot % C4) * 4;
-            *(v4f*)(lds + row * S + col) = stage_reg[i];
+            *(v4f*)(buf + row * XS + col) = stage_reg[i];
         }
     };
 
-    issue_loads(0);
+    // ---- weights and descriptors of one chunk.  The four 16-byte loads cover
+    // 16 entries; entries past the chunk's own belong to later chunks or to the
+    // array's slack and are never used.
+    const uint32_t* wo = woff + (size_t)bsafe * (n_chunks + 1);
+    const Record* recs = (const Record*)__builtin_assume_aligned(records, 64) + (size_t)bsafe * n_chunks;
+    auto load_weights = [&](int c, v4f (&w)[4]) {
+        const uint32_t e0 = __builtin_amdgcn_readfirstlane(wo[c]);
+        const v4f* src = (const v4f*)(wts + (size_t)e0 * 64) + lane;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) w[q4] = src[q4 * 64];
+    };
+
+    v4f w_cur[4], w_nxt[4];
+    Record r_cur, r_nxt;
+    if (VEC) {
+        issue_x_direct(0, lds);
+    } else {
+        issue_x_regs(0);
+        write_x_regs(lds);
+    }
+    load_weights(0, w_cur);
+    r_cur = recs[0];
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wave's LDS-bound loads have landed
+    __syncthreads();
+
     for (int c = 0; c < n_chunks; ++c) {
-        if (c) __syncthreads();          // every wave has finished reading the previous chunk
-        write_lds();
-        __syncthreads();
-        if (c + 1 < n_chunks) issue_loads(c + 1);   // in flight while this chunk is consumed
+        const float* xbuf = lds + (DB && (c & 1) ? XBUF : 0);
+        const bool more = c + 1 < n_chunks;
+        if (more) {                          // in flight while this chunk is multiplied
+            if (VEC) {
+                if (DB) issue_x_direct(c + 1, lds + ((c & 1) ? 0 : XBUF));
+            } else {
+                issue_x_regs(c + 1);
+            }
+            load_weights(c + 1, w_nxt);
+            r_nxt = recs[c + 1];
+        }
 
         if (active) {
-            const int c32 = c * (KC / 32);
-            const int c32e = min(c32 + KC / 32, n_chunks32);
-            uint32_t e = __builtin_amdgcn_readfirstlane(cp[c32]);
-            const uint32_t e1 = __builtin_amdgcn_readfirstlane(cp[c32e]);
-
-            // Data of entry `en` whose descriptor `ent` is already in a scalar register.
-            auto load = [&](uint32_t en, uint32_t ent, Stage<P>& s) {
-                s.wv = wts[(size_t)en * 64 + lane];
-                const int off = ((ent >> 8) & (C4 - 1)) * 16;
+            const char* lds_lane = (const char*)xbuf + lane * (XS * 4);
+            v4f xa[P], xb[P];
+            auto read_x = [&](uint32_t d, v4f (&xv)[P]) {
+                const int off = (d >> 8) * 16;           // kb4 within the chunk: < 16
 #pragma unroll
-                for (int p = 0; p < P; ++p) s.xv[p] = *(const v4f*)(lds_lane + off + p * (64 * S * 4));
+                for (int p = 0; p < P; ++p) xv[p] = *(const v4f*)(lds_lane + off + p * (64 * XS * 4));
             };
-            auto compute = [&](const Stage<P>& s, uint32_t m) {
-                if (m & 1u) group_fma<P, 0>(s, acc);
-                if (m & 2u) group_fma<P, 1>(s, acc);
-                if (m & 4u) group_fma<P, 2>(s, acc);
-                if (m & 8u) group_fma<P, 3>(s, acc);
-            };
-
-            if (e < e1) {
-                // Descriptors run two entries ahead and data one entry ahead of
-                // the arithmetic.  Reads past e1 stay inside the buffers' slack
-                // and inside the LDS tile; their values are never used.
-                uint32_t ent_cur = entries[e], ent_nxt = entries[e + 1];
-                Stage<P> a, b;
-                load(e, ent_cur, a);
-                for (;;) {
-                    uint32_t ent_nn = entries[e + 2];
-                    load(e + 1, ent_nxt, b);
-                    compute(a, ent_cur);
-                    ent_cur = ent_nxt;
-                    ent_nxt = ent_nn;
-                    if (++e >= e1) break;
-                    ent_nn = entries[e + 2];
-                    load(e + 1, ent_nxt, a);
-                    compute(b, ent_cur);
-                    ent_cur = ent_nxt;
-                    ent_nxt = ent_nn;
-                    if (++e >= e1) break;
-                }
+            // Entries are compacted at the front of the record; the first zero
+            // descriptor ends the chunk.  Activations run one entry ahead.
+#define SBN_ENTRY(Q, XC, XN)                                                   \
+    if (__builtin_expect(r_cur.d[Q] == 0, 0)) goto chunk_done;                 \
+    if (Q + 1 < 16) read_x(r_cur.d[(Q + 1) & 15], XN);                         \
+    entry_fma<P, NA, (Q) & 3>(r_cur.d[Q], w_cur[(Q) >> 2], XC, acc);
+            read_x(r_cur.d[0], xa);
+            SBN_ENTRY(0, xa, xb)
+            SBN_ENTRY(1, xb, xa)
+            SBN_ENTRY(2, xa, xb)
+            SBN_ENTRY(3, xb, xa)
+            SBN_ENTRY(4, xa, xb)
+            SBN_ENTRY(5, xb, xa)
+            SBN_ENTRY(6, xa, xb)
+            SBN_ENTRY(7, xb, xa)
+            SBN_ENTRY(8, xa, xb)
+            SBN_ENTRY(9, xb, xa)
+            SBN_ENTRY(10, xa, xb)
+            SBN_ENTRY(11, xb, xa)
+            SBN_ENTRY(12, xa, xb)
+            SBN_ENTRY(13, xb, xa)
+            SBN_ENTRY(14, xa, xb)
+            SBN_ENTRY(15, xb, xa)
+#undef SBN_ENTRY
+        chunk_done:;
+        }
+        if (more) {
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) w_cur[q4] = w_nxt[q4];
+            r_cur = r_nxt;
+            if (!DB) {                       // single buffer: refill it once everybody has finished reading
+                __syncthreads();
+                if (VEC)
+                    issue_x_direct(c + 1, lds);
+                else
+                    write_x_regs(lds);
             }
         }
+        // every wave is done with this chunk's tile and its own loads of the next one have landed
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
     }
 
-    // ---- epilogue: bias, activation, store 4 channels (16 bytes) per group
-    if (!active) return;
-    const int ch_base = bundle * 16;
+    // ---- epilogue: partial sums, bias, activation; transpose through LDS
+    // (the barrier that ended the last chunk makes the tile memory reusable)
+    if (active) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const int ch = ch_base + g * 4;
-        if (ch >= N) break;
-        const v4f b = *(const v4f*)(bias + ch);
+        for (int g = 0; g < 4; ++g) {
+            const v4f b = *(const v4f*)(bias + bundle * 16 + g * 4);
 #pragma unroll
-        for (int p = 0; p < P; ++p) {
-            const long long pix = pix0 + p * 64 + lane;
-            if (pix < M) {
-                v4f o = acc[p][g] + b;
+            for (int p = 0; p < P; ++p) {
+                v4f o = acc[p][g][0];
+#pragma unroll
+                for (int a = 1; a < NA; ++a) o += acc[p][g][a];
+                o += b;
                 if (act == SBN_ACT_RELU) {
                     o.x = fmaxf(o.x, 0.f);
                     o.y = fmaxf(o.y, 0.f);
                     o.z = fmaxf(o.z, 0.f);
                     o.w = fmaxf(o.w, 0.f);
                 }
-                *(v4f*)(y + pix * N + ch) = o;
+                *(v4f*)(lds + (p * 64 + lane) * S + wave * 16 + g * 4) = o;
             }
         }
     }
+    __syncthreads();
+    const int ch_base = col_tile * 64;
+#pragma unroll
+    for (int i = 0; i < T * 16 / 256; ++i) {
+        const int slot = i * 256 + threadIdx.x;
+        const int row = slot >> 4, col = (slot & 15) * 4;
+        const long long pix = pix0 + row;
+        if (pix < M && ch_base + col < N) *(v4f*)(y + pix * N + ch_base + col) = *(const v4f*)(lds + row * S + col);
+    }
 }
 
-template <int P, int KC, bool VEC>
+template <int P, int NA, int RS, bool VEC>
 int launch(const sbn_packed* p, const float* x, float* y, long long M, hipStream_t st)
 {
     const sbn::DeviceLayout& L = p->dev;
@@ -215,9 +319,9 @@ int launch(const sbn_packed* p, const float* x, float* y, long long M, hipStream
     const int n_col_tiles = (L.n_bundles + 3) / 4;
     const long long grid = ((n_pix_tiles + 7) / 8) * 8 * n_col_tiles;
     if (grid > 0x7FFFFFFFll) return sbn::fail(SBN_EINVAL, "too many pixels for one launch (%lld)", M);
-    hipLaunchKernelGGL((conv1x1_kernel<P, KC, VEC>), dim3((unsigned)grid), dim3(256), 0, st, x, y, L.d_entries,
-                       L.d_wts, L.d_chunk_ptr32, L.d_bias, M, p->c_in, p->c_out, L.n_bundles, L.n_chunks32,
-                       n_col_tiles, (int)n_pix_tiles, p->act);
+    hipLaunchKernelGGL((conv1x1_kernel<P, NA, RS, VEC>), dim3((unsigned)grid), dim3(256), 0, st, x, y, L.d_records,
+                       L.d_woff, L.d_wts, L.d_bias, M, p->c_in, p->c_out, L.n_bundles, L.n_chunks, n_col_tiles,
+                       (int)n_pix_tiles, p->act);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return sbn::fail(SBN_EHIP, "conv1x1 launch: %s", hipGetErrorString(e));
     return SBN_OK;
@@ -231,14 +335,23 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
 {
     hipStream_t st = (hipStream_t)stream;
     const bool vec = p->c_in % 4 == 0;
-    const bool kc32 = p->c_in <= 32;
-    // pixel sets per wave: two when there are enough pixel tiles to fill the chip
-    const int n_col_tiles = (p->dev.n_bundles + 3) / 4;
-    const long long wgs_p2 = ((M + 127) / 128) * n_col_tiles;
-    const bool p2 = wgs_p2 >= 1024;
-    if (!vec) return kc32 ? launch<1, 32, false>(p, x, y, M, st) : launch<1, 64, false>(p, x, y, M, st);
-    if (kc32) return p2 ? launch<2, 32, true>(p, x, y, M, st) : launch<1, 32, true>(p, x, y, M, st);
-    return p2 ? launch<2, 64, true>(p, x, y, M, st) : launch<1, 64, true>(p, x, y, M, st);
+    const bool k32 = p->c_in <= 32;
+    static const int force = getenv("SBN_K1_VARIANT") ? atoi(getenv("SBN_K1_VARIANT")) : 0;   // benchmarking override
+    if (!vec) return k32 ? launch<1, 2, 9, false>(p, x, y, M, st) : launch<1, 2, 17, false>(p, x, y, M, st);
+    if (k32) {
+        // one chunk, bound by HBM: 128 pixels per workgroup when there are plenty
+        const bool p2 = force ? force / 10 == 2 : M >= 128 * 1024;
+        return p2 ? launch<2, 1, 9, true>(p, x, y, M, st) : launch<1, 2, 9, true>(p, x, y, M, st);
+    }
+    switch (force) {
+    case 11: return launch<1, 1, 17, true>(p, x, y, M, st);
+    case 12: return launch<1, 2, 17, true>(p, x, y, M, st);
+    case 14: return launch<1, 4, 17, true>(p, x, y, M, st);
+    case 21: return launch<2, 1, 17, true>(p, x, y, M, st);
+    case 22: return launch<2, 2, 17, true>(p, x, y, M, st);
+    default: break;
+    }
+    return launch<1, 2, 17, true>(p, x, y, M, st);
 }
 
 }  // namespace sbn

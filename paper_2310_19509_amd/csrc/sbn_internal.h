@@ -20,32 +20,38 @@ void clear_error();
 // The canonical rows (one per output group of `go` filters) are regrouped for
 // the kernels into BUNDLES of kBundleGroups consecutive groups of 4 filters.
 // A bundle walks the union of its groups' kept 4-channel pieces in ascending
-// channel order; an ENTRY is one such piece:
-//     entry = (kb4 << 8) | present_mask        kb4 = first channel / 4
-// bit g of present_mask says that group g of the bundle keeps the piece.  The
-// weights of an entry are stored for all groups of the bundle (zeros where
-// absent) so that one 64-lane load yields [g][ci][co] for every group:
-//     1x1:  wts[entry][g][ci][co]                 64 floats per entry
-//     3x3:  wts[entry][tap][g][ci][co]            9*64 floats per entry
-// chunk_ptr32[bundle][c] is the first entry of the bundle whose channel is
-// >= 32*c (c = 0 .. ceil(c_in/32)), as a global entry index.
+// channel order; an ENTRY is one such piece.  Per bundle and per chunk of 64
+// input channels there is one fixed-size RECORD of 16 descriptors (64 bytes):
+//     records[bundle][chunk][q] = (kb4_in_chunk << 8) | present_mask   q < n
+//                               = 0                                    q >= n
+// kb4_in_chunk = (first channel of the piece - 64*chunk) / 4; bit g of
+// present_mask says that group g of the bundle keeps the piece; n <= 16 is
+// the number of entries of the bundle inside the chunk.  woff[bundle][chunk]
+// is the global index of the chunk's first entry (woff[bundle][n_chunks] its
+// end).  The weights of an entry are stored for all groups of the bundle
+// (zeros where absent), transposed so that a 16-byte load per lane yields the
+// four input channels of one output channel:
+//     1x1:  wts[entry][g][co][ci]                 64 floats per entry
+//     3x3:  wts[entry][tap][g][co][ci]            9*64 floats per entry
 constexpr int kBundleGroups = 4;                       // groups of 4 filters per bundle
 constexpr int kBundleChannels = 4 * kBundleGroups;     // 16 output channels per bundle
+constexpr int kChunk = 64;                             // input channels per record
+constexpr int kSlots = kChunk / 4;                     // descriptors per record
 
 struct DeviceLayout {
     int n_bundles = 0;
-    int n_chunks32 = 0;
+    int n_chunks = 0;                     // ceil(c_in / 64)
     size_t n_entries = 0;
-    // host staging (kept so that sbn_free needs no device reads; small)
-    std::vector<uint32_t> entries;
+    // host staging
+    std::vector<uint32_t> records;        // [n_bundles][n_chunks][16]
+    std::vector<uint32_t> woff;           // [n_bundles][n_chunks + 1]
     std::vector<float> wts;
-    std::vector<uint32_t> chunk_ptr32;
     std::vector<float> bias_padded;       // [n_bundles * 16], zeros when no bias
     // device copies (one allocation)
     void* d_blob = nullptr;
-    uint32_t* d_entries = nullptr;
+    uint32_t* d_records = nullptr;
+    uint32_t* d_woff = nullptr;
     float* d_wts = nullptr;
-    uint32_t* d_chunk_ptr32 = nullptr;
     float* d_bias = nullptr;
 };
 

@@ -18,54 +18,54 @@ void build_device_layout(sbn_packed* p)
     const int taps = p->kh * p->kw, go = p->go, gi = p->gi;
     const int n_groups4 = p->c_out / 4;                              // go is 4 or 8
     L.n_bundles = (n_groups4 + kBundleGroups - 1) / kBundleGroups;
-    L.n_chunks32 = (p->c_in + 31) / 32;
+    L.n_chunks = (p->c_in + kChunk - 1) / kChunk;
     const size_t wstride = (size_t)taps * kBundleGroups * 16;        // floats per entry
     const size_t blk = (size_t)taps * gi * go;
 
-    L.entries.clear();
+    L.records.assign((size_t)L.n_bundles * L.n_chunks * kSlots, 0u);
+    L.woff.assign((size_t)L.n_bundles * (L.n_chunks + 1), 0u);
     L.wts.clear();
-    L.chunk_ptr32.assign((size_t)L.n_bundles * (L.n_chunks32 + 1), 0u);
+    size_t n_entries = 0;
 
     const int sub = go / 4;                                          // 4-filter groups per canonical row
     for (int b = 0; b < L.n_bundles; ++b) {
-        // kb4 -> entry position (within this bundle), ascending by construction of std::map
-        std::map<int, size_t> pos;
+        // kb4 -> (entry index, present mask); std::map keeps channels ascending
+        std::map<int, std::pair<size_t, uint32_t>> pos;
         const int g_lo = b * kBundleGroups, g_hi = std::min(n_groups4, g_lo + kBundleGroups);
         for (int g4 = g_lo; g4 < g_hi; ++g4) {
             const int row = g4 / sub;
             for (uint32_t e = p->row_ptr[(size_t)row]; e < p->row_ptr[(size_t)row + 1]; ++e)
-                for (int c = 0; c < gi; ++c) pos[(p->kidx[e] + c) / 4] = 0;
+                for (int c = 0; c < gi; ++c) pos[(p->kidx[e] + c) / 4].second |= 1u << (g4 - g_lo);
         }
-        const size_t first = L.entries.size();
-        size_t n = 0;
-        for (auto& kv : pos) {
-            kv.second = first + n++;
-            L.entries.push_back((uint32_t)kv.first << 8);
-        }
-        L.wts.resize((first + n) * wstride, 0.0f);
+        const size_t first = n_entries;
+        for (auto& kv : pos) kv.second.first = n_entries++;
+        L.wts.resize(n_entries * wstride, 0.0f);
         for (int g4 = g_lo; g4 < g_hi; ++g4) {
             const int row = g4 / sub, s = g4 % sub, g = g4 - g_lo;
             for (uint32_t e = p->row_ptr[(size_t)row]; e < p->row_ptr[(size_t)row + 1]; ++e)
                 for (int c = 0; c < gi; ++c) {
                     const int ch = p->kidx[e] + c;
-                    const size_t en = pos[ch / 4];
-                    L.entries[en] |= 1u << g;
+                    const size_t en = pos[ch / 4].first;
                     for (int t = 0; t < taps; ++t)
                         for (int co = 0; co < 4; ++co)
-                            L.wts[en * wstride + (((size_t)t * kBundleGroups + g) * 4 + (ch % 4)) * 4 + co] =
+                            L.wts[en * wstride + (((size_t)t * kBundleGroups + g) * 4 + co) * 4 + (ch % 4)] =
                                 p->vals[e * blk + ((size_t)t * gi + c) * go + (size_t)s * 4 + co];
                 }
         }
-        // chunk pointers: first entry with channel >= 32*c
-        uint32_t* cp = &L.chunk_ptr32[(size_t)b * (L.n_chunks32 + 1)];
-        size_t en = first;
-        for (int c = 0; c <= L.n_chunks32; ++c) {
-            while (en < first + n && (int)(L.entries[en] >> 8) * 4 < 32 * c) ++en;
-            cp[c] = (uint32_t)en;
+        // records and chunk offsets
+        uint32_t* wo = &L.woff[(size_t)b * (L.n_chunks + 1)];
+        std::vector<int> fill((size_t)L.n_chunks, 0);
+        for (int c = 0; c <= L.n_chunks; ++c) wo[c] = (uint32_t)n_entries;
+        for (const auto& kv : pos) {
+            const int c = kv.first / kSlots, q = fill[(size_t)c]++;
+            L.records[((size_t)b * L.n_chunks + c) * kSlots + q] = ((uint32_t)(kv.first % kSlots) << 8) | kv.second.second;
+            wo[c] = std::min(wo[c], (uint32_t)kv.second.first);
         }
-        cp[L.n_chunks32] = (uint32_t)(first + n);
+        // empty chunks start where the next non-empty one does
+        for (int c = L.n_chunks - 1; c >= 0; --c) wo[c] = std::min(wo[c], wo[c + 1]);
+        (void)first;
     }
-    L.n_entries = L.entries.size();
+    L.n_entries = n_entries;
     L.bias_padded.assign((size_t)L.n_bundles * kBundleChannels, 0.0f);
     std::copy(p->bias.begin(), p->bias.end(), L.bias_padded.begin());
 }
@@ -83,13 +83,14 @@ int upload_device_layout(sbn_packed* p)
     (void)hipGetDevice(&prev);
     if ((e = hipSetDevice(p->device)) != hipSuccess) return fail(SBN_EHIP, "hipSetDevice: %s", hipGetErrorString(e));
 
-    // one allocation; +256 floats of slack after the weights so that the
-    // kernels' one-entry-ahead prefetch never leaves the buffer
-    const size_t b_entries = align256((L.entries.size() + 64) * sizeof(uint32_t));
-    const size_t b_wts = align256((L.wts.size() + 9 * 64) * sizeof(float));
-    const size_t b_cp = align256(L.chunk_ptr32.size() * sizeof(uint32_t));
+    // One allocation.  The kernels fetch the weights of a whole record (up to
+    // 16 entries) at once, so the weight array carries 16 entries of slack.
+    const size_t wstride = (size_t)p->kh * p->kw * kBundleGroups * 16;
+    const size_t b_rec = align256(L.records.size() * sizeof(uint32_t));
+    const size_t b_woff = align256(L.woff.size() * sizeof(uint32_t));
+    const size_t b_wts = align256((L.wts.size() + kSlots * wstride) * sizeof(float));
     const size_t b_bias = align256(L.bias_padded.size() * sizeof(float));
-    const size_t total = b_entries + b_wts + b_cp + b_bias;
+    const size_t total = b_rec + b_woff + b_wts + b_bias;
     char* blob = nullptr;
     if ((e = hipMalloc((void**)&blob, total)) != hipSuccess) {
         (void)hipSetDevice(prev);
@@ -97,22 +98,21 @@ int upload_device_layout(sbn_packed* p)
     }
     std::vector<char> host(total, 0);
     size_t off = 0;
-    std::memcpy(host.data() + off, L.entries.data(), L.entries.size() * sizeof(uint32_t));
-    L.d_entries = (uint32_t*)(blob + off);
-    off += b_entries;
+    std::memcpy(host.data() + off, L.records.data(), L.records.size() * sizeof(uint32_t));
+    L.d_records = (uint32_t*)(blob + off);
+    off += b_rec;
+    std::memcpy(host.data() + off, L.woff.data(), L.woff.size() * sizeof(uint32_t));
+    L.d_woff = (uint32_t*)(blob + off);
+    off += b_woff;
     std::memcpy(host.data() + off, L.wts.data(), L.wts.size() * sizeof(float));
     L.d_wts = (float*)(blob + off);
     off += b_wts;
-    std::memcpy(host.data() + off, L.chunk_ptr32.data(), L.chunk_ptr32.size() * sizeof(uint32_t));
-    L.d_chunk_ptr32 = (uint32_t*)(blob + off);
-    off += b_cp;
     std::memcpy(host.data() + off, L.bias_padded.data(), L.bias_padded.size() * sizeof(float));
     L.d_bias = (float*)(blob + off);
     e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {
         (void)hipFree(blob);
-        L.d_entries = nullptr;
         return fail(SBN_EHIP, "hipMemcpy of packed layer: %s", hipGetErrorString(e));
     }
     L.d_blob = blob;
