@@ -53,28 +53,34 @@ __device__ __forceinline__ v4f mfma_bcast(float w, float x, v4f c)
     return __builtin_amdgcn_mfma_f32_4x4x1f32(w, x, c, 4, ABID, 0);
 }
 
-// acc[p][g][a]: pixel set p, group g, partial sum a (input channel ci goes to a = ci % NA)
-template <int P, int NA, int Q4, int G>
+// acc[p][g][a]: pixel set p, group g, partial sum a.  An MFMA that adds to the
+// result of one issued fewer than three MFMAs earlier stalls the matrix pipe for
+// every wave, so the four input channels of a piece rotate over NA partial sums;
+// with NA = 3 the rotation also advances with the entry slot Q so that the
+// distance stays three across entries.
+template <int P, int NA, int Q, int G>
 __device__ __forceinline__ void group_fma(const v4f& w, const v4f (&xv)[P], v4f (&acc)[P][4][NA])
 {
+    constexpr int R = NA == 3 ? Q % 3 : 0;
+    constexpr int AB = (Q & 3) * 4 + G;
 #pragma unroll
-    for (int p = 0; p < P; ++p) acc[p][G][0 % NA] = mfma_bcast<Q4 * 4 + G>(w.x, xv[p].x, acc[p][G][0 % NA]);
+    for (int p = 0; p < P; ++p) acc[p][G][(0 + R) % NA] = mfma_bcast<AB>(w.x, xv[p].x, acc[p][G][(0 + R) % NA]);
 #pragma unroll
-    for (int p = 0; p < P; ++p) acc[p][G][1 % NA] = mfma_bcast<Q4 * 4 + G>(w.y, xv[p].y, acc[p][G][1 % NA]);
+    for (int p = 0; p < P; ++p) acc[p][G][(1 + R) % NA] = mfma_bcast<AB>(w.y, xv[p].y, acc[p][G][(1 + R) % NA]);
 #pragma unroll
-    for (int p = 0; p < P; ++p) acc[p][G][2 % NA] = mfma_bcast<Q4 * 4 + G>(w.z, xv[p].z, acc[p][G][2 % NA]);
+    for (int p = 0; p < P; ++p) acc[p][G][(2 + R) % NA] = mfma_bcast<AB>(w.z, xv[p].z, acc[p][G][(2 + R) % NA]);
 #pragma unroll
-    for (int p = 0; p < P; ++p) acc[p][G][3 % NA] = mfma_bcast<Q4 * 4 + G>(w.w, xv[p].w, acc[p][G][3 % NA]);
+    for (int p = 0; p < P; ++p) acc[p][G][(3 + R) % NA] = mfma_bcast<AB>(w.w, xv[p].w, acc[p][G][(3 + R) % NA]);
 }
 
-template <int P, int NA, int Q4>
+template <int P, int NA, int Q>
 __device__ __forceinline__ void entry_fma(uint32_t m, const v4f& w, const v4f (&xv)[P], v4f (&acc)[P][4][NA])
 {
     // a taken branch costs the wave tens of cycles: keep "present" the fall-through path
-    if (__builtin_expect((m & 1u) != 0, 1)) group_fma<P, NA, Q4, 0>(w, xv, acc);
-    if (__builtin_expect((m & 2u) != 0, 1)) group_fma<P, NA, Q4, 1>(w, xv, acc);
-    if (__builtin_expect((m & 4u) != 0, 1)) group_fma<P, NA, Q4, 2>(w, xv, acc);
-    if (__builtin_expect((m & 8u) != 0, 1)) group_fma<P, NA, Q4, 3>(w, xv, acc);
+    if (__builtin_expect((m & 1u) != 0, 1)) group_fma<P, NA, Q, 0>(w, xv, acc);
+    if (__builtin_expect((m & 2u) != 0, 1)) group_fma<P, NA, Q, 1>(w, xv, acc);
+    if (__builtin_expect((m & 4u) != 0, 1)) group_fma<P, NA, Q, 2>(w, xv, acc);
+    if (__builtin_expect((m & 8u) != 0, 1)) group_fma<P, NA, Q, 3>(w, xv, acc);
 }
 
 struct Record {
@@ -136,16 +142,16 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
     // pixel and channels past c_in fetch some valid address instead: no entry
     // ever reads those channels and a lane only ever reads its own pixel's row.
     constexpr int NI = (T * RS / 64 + 3) / 4;          // instructions per wave
-    const float* grow[VEC ? NI : 1];           // first channel of the slot's pixel
+    const float* xtile = x + pix0 * K;                      // uniform
+    const int rows_valid = (int)(M - pix0 < T ? M - pix0 : T);
+    uint32_t grow[VEC ? NI : 1];               // float offset of the slot's pixel row from xtile
     int gcol[VEC ? NI : 1];                    // channel offset of the slot inside a chunk
     if (VEC) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int g = ((i * 4 + wave) * 64 + lane) % (T * RS);
             const int row = g / RS, col = g % RS;
-            long long pix = pix0 + row;
-            pix = pix < M ? pix : M - 1;
-            grow[i] = x + pix * K;
+            grow[i] = (uint32_t)(row < rows_valid ? row : rows_valid - 1) * (uint32_t)K;
             gcol[i] = (col < RS - 1 ? col : RS - 2) * 4;
         }
     }
@@ -154,7 +160,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
         for (int i = 0; i < NI; ++i) {
             if ((i * 4 + wave) * 64 < T * RS) {
                 const int ch = min(c * KC + gcol[i], K - 4);      // keep the 16-byte read inside the row
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(grow[i] + ch),
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xtile + (grow[i] + (uint32_t)ch)),
                                                  (__attribute__((address_space(3))) void*)(buf + (i * 4 + wave) * 256),
                                                  16, 0, 0);
             }
@@ -203,6 +209,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
 
     v4f w_cur[4], w_nxt[4];
     Record r_cur, r_nxt;
+    SBN_TS(0)
     if (VEC) {
         issue_x_direct(0, lds);
     } else {
@@ -213,6 +220,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
     r_cur = recs[0];
     __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wave's LDS-bound loads have landed
     __syncthreads();
+    SBN_TS(1)
 
     for (int c = 0; c < n_chunks; ++c) {
         const float* xbuf = lds + (DB && (c & 1) ? XBUF : 0);
@@ -226,6 +234,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
             load_weights(c + 1, w_nxt);
             r_nxt = recs[c + 1];
         }
+        SBN_TS(2 + c * 4)
 
         if (active) {
             const char* lds_lane = (const char*)xbuf + lane * (XS * 4);
@@ -240,7 +249,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
 #define SBN_ENTRY(Q, XC, XN)                                                   \
     if (__builtin_expect(r_cur.d[Q] == 0, 0)) goto chunk_done;                 \
     if (Q + 1 < 16) read_x(r_cur.d[(Q + 1) & 15], XN);                         \
-    entry_fma<P, NA, (Q) & 3>(r_cur.d[Q], w_cur[(Q) >> 2], XC, acc);
+    entry_fma<P, NA, Q>(r_cur.d[Q], w_cur[(Q) >> 2], XC, acc);
             read_x(r_cur.d[0], xa);
             SBN_ENTRY(0, xa, xb)
             SBN_ENTRY(1, xb, xa)
@@ -261,6 +270,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
 #undef SBN_ENTRY
         chunk_done:;
         }
+        SBN_TS(3 + c * 4)
         if (more) {
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) w_cur[q4] = w_nxt[q4];
@@ -275,7 +285,9 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
         }
         // every wave is done with this chunk's tile and its own loads of the next one have landed
         __builtin_amdgcn_s_waitcnt(0x0F70);
+        SBN_TS(4 + c * 4)
         __syncthreads();
+        SBN_TS(5 + c * 4)
     }
 
     // ---- epilogue: partial sums, bias, activation; transpose through LDS
@@ -309,6 +321,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
         const long long pix = pix0 + row;
         if (pix < M && ch_base + col < N) *(v4f*)(y + pix * N + ch_base + col) = *(const v4f*)(lds + row * S + col);
     }
+    SBN_TS(101)
 }
 
 template <int P, int NA, int RS, bool VEC>
@@ -346,6 +359,7 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
     switch (force) {
     case 11: return launch<1, 1, 17, true>(p, x, y, M, st);
     case 12: return launch<1, 2, 17, true>(p, x, y, M, st);
+    case 13: return launch<1, 3, 17, true>(p, x, y, M, st);
     case 14: return launch<1, 4, 17, true>(p, x, y, M, st);
     case 21: return launch<2, 1, 17, true>(p, x, y, M, st);
     case 22: return launch<2, 2, 17, true>(p, x, y, M, st);

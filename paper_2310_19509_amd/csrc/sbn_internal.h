@@ -32,7 +32,7 @@ void clear_error();
 // (zeros where absent), transposed so that a 16-byte load per lane yields the
 // four input channels of one output channel:
 //     1x1:  wts[entry][g][co][ci]                 64 floats per entry
-//     3x3:  wts[entry][tap][g][co][ci]            9*64 floats per entry
+//     3x3:  wts[entry][tap][g][ci][co]            9*64 floats per entry (4-byte loads per lane)
 constexpr int kBundleGroups = 4;                       // groups of 4 filters per bundle
 constexpr int kBundleChannels = 4 * kBundleGroups;     // 16 output channels per bundle
 constexpr int kChunk = 64;                             // input channels per record
@@ -53,6 +53,7 @@ struct DeviceLayout {
     uint32_t* d_woff = nullptr;
     float* d_wts = nullptr;
     float* d_bias = nullptr;
+    float* d_zeros = nullptr;             // 64 zero floats (source of out-of-image activation slots)
 };
 
 }  // namespace sbn

@@ -47,9 +47,12 @@ void build_device_layout(sbn_packed* p)
                     const int ch = p->kidx[e] + c;
                     const size_t en = pos[ch / 4].first;
                     for (int t = 0; t < taps; ++t)
-                        for (int co = 0; co < 4; ++co)
-                            L.wts[en * wstride + (((size_t)t * kBundleGroups + g) * 4 + co) * 4 + (ch % 4)] =
+                        for (int co = 0; co < 4; ++co) {
+                            // 1x1: [g][co][ci] (16-byte loads per lane); 3x3: [tap][g][ci][co] (4-byte loads)
+                            const size_t inner = taps == 1 ? (size_t)co * 4 + (ch % 4) : (size_t)(ch % 4) * 4 + co;
+                            L.wts[en * wstride + ((size_t)t * kBundleGroups + g) * 16 + inner] =
                                 p->vals[e * blk + ((size_t)t * gi + c) * go + (size_t)s * 4 + co];
+                        }
                 }
         }
         // records and chunk offsets
@@ -89,7 +92,7 @@ int upload_device_layout(sbn_packed* p)
     const size_t b_rec = align256(L.records.size() * sizeof(uint32_t));
     const size_t b_woff = align256(L.woff.size() * sizeof(uint32_t));
     const size_t b_wts = align256((L.wts.size() + kSlots * wstride) * sizeof(float));
-    const size_t b_bias = align256(L.bias_padded.size() * sizeof(float));
+    const size_t b_bias = align256((L.bias_padded.size() + 64) * sizeof(float));   // + a block of zeros
     const size_t total = b_rec + b_woff + b_wts + b_bias;
     char* blob = nullptr;
     if ((e = hipMalloc((void**)&blob, total)) != hipSuccess) {
@@ -109,6 +112,7 @@ int upload_device_layout(sbn_packed* p)
     off += b_wts;
     std::memcpy(host.data() + off, L.bias_padded.data(), L.bias_padded.size() * sizeof(float));
     L.d_bias = (float*)(blob + off);
+    L.d_zeros = L.d_bias + L.bias_padded.size();
     e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {

@@ -1,0 +1,154 @@
+"""Layer chaining on the GPU: sparse pointwise layers, dense depthwise 3x3 + ReLU between
+them, global average pool and a dense classifier, checked layer by layer against the oracle
+(each oracle layer is fed the GPU's previous output) and end to end on a small input."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2310_19509_amd as S
+from oracle import reference as R
+import workloads as W
+from helpers import assert_within_bound
+
+pytestmark = pytest.mark.gpu
+
+
+def build_stack(chans, hw, batch, pct, seed, strides):
+    """Rearranged, pruned pointwise layers with depthwise layers in front of each."""
+    L = len(chans) - 1
+    pws = [dict(kind=S.SBN_CONV1X1, w=W.he_weights(seed + i, chans[i + 1], 1, 1, chans[i]), go=4, gi=4)
+           for i in range(L)]
+    perms = S.sbn_rearrange(pws, [-1] + list(range(L - 1)), pct, seed=seed, max_iters=300,
+                            keep_output_order=[0] * (L - 1) + [1])
+    items, meta = [], []
+    pin = None
+    for i in range(L):
+        dw_w = W.normal_weights(seed + 50 + i, (chans[i], 3, 3), 0.4)
+        dw_b = W.small_bias(seed + 70 + i, chans[i])
+        items.append(S.dw_item(dw_w, dw_b, stride=strides[i], act=S.SBN_ACT_RELU))
+        meta.append(dict(kind="dw", w=dw_w, b=dw_b, stride=strides[i], order=pin))
+        b = W.small_bias(seed + 90 + i, chans[i + 1])
+        wp = R.permute_weights(pws[i]["w"], perms[i], pin)
+        mask = S.sbn_prune_magnitude(wp, S.SBN_CONV1X1, 4, 4, pct)
+        p = S.sbn_pack(S.SBN_CONV1X1, pws[i]["w"], 4, 4, mask=mask, bias=b, perm_out=perms[i], perm_in=pin,
+                       act=S.SBN_ACT_RELU)
+        items.append(S.sparse_item(p))
+        meta.append(dict(kind="pw", w=pws[i]["w"], b=b, mask=mask, po=perms[i], pi=pin))
+        pin = perms[i]
+    return items, meta
+
+
+def oracle_item(m, x):
+    if m["kind"] == "dw":
+        w, b = m["w"], m["b"]
+        if m["order"] is not None:
+            w, b = w[m["order"]], b[m["order"]]
+        return R.dwconv3x3_nhwc(x, w, b, stride=m["stride"], act=R.ACT_RELU)
+    if m["kind"] == "pw":
+        return R.sparse_conv_reference(x, m["w"], m["mask"], 4, 4, bias=m["b"], perm_out=m["po"], perm_in=m["pi"],
+                                       act=R.ACT_RELU)
+    if m["kind"] == "pool":
+        y = R.avgpool_nhwc(x)[:, None, None, :]
+        return y, None
+    raise AssertionError
+
+
+def test_chain_layer_by_layer_and_end_to_end():
+    chans, strides = [16, 32, 64, 64, 24], [1, 2, 1, 2]
+    n, hw = 3, 18
+    items, meta = build_stack(chans, hw, n, 50, 9000, strides)
+    items.append(S.avgpool_item())
+    meta.append(dict(kind="pool"))
+    fc_w = W.he_weights(9100, 12, 1, 1, chans[-1])
+    fc = S.sbn_pack(S.SBN_CONV1X1, fc_w, 4, 4, bias=W.small_bias(9101, 12))       # dense classifier: all blocks kept
+    items.append(S.sparse_item(fc))
+    meta.append(dict(kind="pw", w=fc_w, b=W.small_bias(9101, 12), mask=np.ones((3, chans[-1] // 4), np.uint8),
+                     po=None, pi=None))
+    meta[-1]["act_none"] = True
+    chain = S.sbn_chain_create(items)
+    oh, ow, oc = S.sbn_chain_output_shape(chain, n, hw, hw)
+    assert (oh, ow, oc) == (1, 1, 12)
+    ws = torch.empty(S.sbn_chain_workspace(chain, n, hw, hw) // 4, device="cuda")
+    x = W.uniform_activation(9200, (n, hw, hw, chans[0]))
+    xd = torch.from_numpy(x).cuda()
+    yd = torch.full((n, 1, 1, 12), float("nan"), device="cuda")
+    # shapes of every item's output, to allocate the per-layer taps
+    shapes, h, c = [], hw, chans[0]
+    for m in meta:
+        if m["kind"] == "dw":
+            h = (h - 1) // m["stride"] + 1
+        elif m["kind"] == "pw":
+            c = m["w"].shape[0]
+        else:
+            h = 1
+        shapes.append((n, h, h, c))
+    taps = [torch.full(s, float("nan"), device="cuda") for s in shapes]
+    S.sbn_pointwise_chain(chain, xd, yd, n, hw, hw, ws, layer_outputs=taps)
+    torch.cuda.synchronize()
+    outs = [t.cpu().numpy() for t in taps]
+    assert np.array_equal(outs[-1], yd.cpu().numpy())
+
+    # teacher-forced: oracle layer l is fed the GPU's output of layer l-1
+    prev = x
+    for i, m in enumerate(meta):
+        if m.get("act_none"):
+            ref, bound = R.sparse_conv_reference(prev, m["w"], m["mask"], 4, 4, bias=m["b"])
+        else:
+            ref, bound = oracle_item(m, prev)
+        if bound is None:       # average pool: fp32 sum of 25 values vs fp64
+            np.testing.assert_allclose(outs[i], ref, rtol=0, atol=1e-5)
+        else:
+            assert_within_bound(outs[i], ref, bound, f"chain item {i} ({m['kind']})")
+        prev = outs[i]
+
+    # end to end in original channel order, no rearrangement, same masks mapped back
+    cur = x
+    for m in meta:
+        if m["kind"] == "dw":
+            cur, _ = R.dwconv3x3_nhwc(cur, m["w"], m["b"], stride=m["stride"], act=R.ACT_RELU)
+        elif m["kind"] == "pool":
+            cur = R.avgpool_nhwc(cur)[:, None, None, :]
+        else:
+            wp = R.permute_weights(m["w"], m["po"], m["pi"])
+            wt = R.unpermute_weights(R.apply_mask(wp, m["mask"], 4, 4), m["po"], m["pi"])
+            cur, _ = R.conv_nhwc(cur, wt, m["b"], act=R.ACT_NONE if m.get("act_none") else R.ACT_RELU)
+    np.testing.assert_allclose(outs[-1], cur, rtol=1e-3, atol=1e-4)
+
+
+def test_chain_rejects_mismatched_orders_and_shapes():
+    w1, w2 = W.he_weights(9300, 16, 1, 1, 8), W.he_weights(9301, 8, 1, 1, 16)
+    po = W.random_permutation(9302, 16)
+    a = S.sbn_pack(S.SBN_CONV1X1, w1, 4, 4, perm_out=po)
+    b_bad = S.sbn_pack(S.SBN_CONV1X1, w2, 4, 4)                    # expects identity order
+    b_ok = S.sbn_pack(S.SBN_CONV1X1, w2, 4, 4, perm_in=po)
+    with pytest.raises(S.SbnError) as ei:
+        S.sbn_chain_create([S.sparse_item(a), S.sparse_item(b_bad)])
+    assert ei.value.code == -2
+    chain = S.sbn_chain_create([S.sparse_item(a), S.sparse_item(b_ok)])
+    with pytest.raises(S.SbnError):
+        S.sbn_chain_create([S.sparse_item(a), S.sparse_item(a)])     # 16 channels out, 8 expected in
+    with pytest.raises(S.SbnError):
+        S.sbn_chain_create([S.sparse_item(a), S.dw_item(np.zeros((8, 3, 3), np.float32))])
+    x = torch.zeros(1, 2, 2, 8, device="cuda")
+    y = torch.zeros(1, 2, 2, 8, device="cuda")
+    with pytest.raises(S.SbnError):
+        S.sbn_pointwise_chain(chain, x, y, 1, 2, 2, None)            # workspace missing
+
+
+def test_chain_with_3x3_layer():
+    w3 = W.he_weights(9400, 16, 3, 3, 8)
+    m3 = S.sbn_prune_magnitude(w3, S.SBN_CONV3X3, 4, 4, 50)
+    a = S.sbn_pack(S.SBN_CONV3X3, w3, 4, 4, mask=m3, stride=2, act=S.SBN_ACT_RELU)
+    w1 = W.he_weights(9401, 8, 1, 1, 16)
+    b = S.sbn_pack(S.SBN_CONV1X1, w1, 4, 4)
+    chain = S.sbn_chain_create([S.sparse_item(a), S.sparse_item(b)])
+    n, hw = 2, 11
+    assert S.sbn_chain_output_shape(chain, n, hw, hw) == (6, 6, 8)
+    ws = torch.empty(S.sbn_chain_workspace(chain, n, hw, hw) // 4, device="cuda")
+    x = W.uniform_activation(9402, (n, hw, hw, 8))
+    yd = torch.empty(n, 6, 6, 8, device="cuda")
+    S.sbn_pointwise_chain(chain, torch.from_numpy(x).cuda(), yd, n, hw, hw, ws)
+    torch.cuda.synchronize()
+    h1, _ = R.sparse_conv_reference(x, w3, m3, 4, 4, stride=2, pad=1, act=R.ACT_RELU)
+    ref, bound = R.conv_nhwc(h1, w1)
+    np.testing.assert_allclose(yd.cpu().numpy(), ref, rtol=1e-4, atol=1e-5)
