@@ -81,6 +81,9 @@ def lib() -> C.CDLL:
     """The loaded library; built first if no libsbn.so exists yet."""
     global _lib
     if _lib is None:
+        # torch ships its own HIP runtime; import it first so that libsbn.so binds to the
+        # runtime that also owns the device memory and streams it is handed
+        import torch  # noqa: F401
         if not os.path.exists(LIB_PATH):
             build()
         l = C.CDLL(LIB_PATH)
