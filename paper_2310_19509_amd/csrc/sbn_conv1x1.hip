@@ -34,8 +34,10 @@ extern "C" int sbn_trace_read(unsigned long long* out)
     return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sbn_trace_buf), sizeof(unsigned long long) * 8 * 4 * 128);
 }
 #define SBN_TS(i)                                                                                         \
-    if (lane == 0 && (blockIdx.x % 200) == 0 && blockIdx.x / 200 < 8)                                      \
-        sbn_trace_buf[((blockIdx.x / 200) * 4 + wave) * 128 + (i)] = __builtin_readcyclecounter();
+    if (lane == 0 && (blockIdx.x % 200) == 0 && blockIdx.x / 200 < 8) {                                    \
+        sbn_trace_buf[((blockIdx.x / 200) * 4 + wave) * 128 + (i)] = __builtin_readcyclecounter();         \
+        if ((i) == 0 || (i) == 101) sbn_trace_buf[((blockIdx.x / 200) * 4 + wave) * 128 + (i) + 10] = wall_clock64(); \
+    }
 #else
 #define SBN_TS(i)
 #endif
@@ -88,11 +90,19 @@ struct Record {
 };
 
 // P: pixel sets of 64 per wave.  NA: partial sums per (pixel set, group).
-// RS: 16-byte slots per staged LDS row, 17 (64 channels + pad) or 9 (32 + pad,
-// for layers with c_in <= 32).  VEC: c_in % 4 == 0, activations go from global
-// memory straight into LDS (global_load_lds_dwordx4); otherwise they are staged
-// through registers with scalar loads.
-template <int P, int NA, int RS, bool VEC>
+// KC: channels staged per chunk, 64, or 32 for layers with c_in <= 32.
+// MULTI: c_in > KC, more than one chunk.  VEC: c_in % 4 == 0 (16-byte
+// activation loads); otherwise scalar loads with zero fill.
+//
+// Activations go global -> registers -> LDS.  (global_load_lds would save the
+// registers, but the compiler then drains the whole vector-memory counter
+// before every LDS read, which serialises the prefetch with the arithmetic.)
+// Two LDS buffers alternate: the loads of chunk c+1 are issued before chunk c
+// is multiplied, land in registers meanwhile, are written to the other buffer
+// afterwards, and one barrier per chunk publishes them.  The prefetch is
+// unconditional (the last chunk fetches itself again): loads issued under a
+// branch would make the compiler wait for them before the first multiply.
+template <int P, int NA, int KC, bool MULTI, bool VEC>
 __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                       const uint32_t* __restrict__ records,
                                                       const uint32_t* __restrict__ woff,
@@ -101,13 +111,12 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
                                                       int n_col_tiles, int n_pix_tiles, int act)
 {
     constexpr int T = 64 * P;                  // pixels per workgroup
-    constexpr int KC = (RS - 1) * 4;           // channels staged per chunk
-    constexpr int XS = RS * 4;                 // staged row stride in floats
+    constexpr int XS = KC + 4;                 // staged row stride in floats
     constexpr int XBUF = T * XS;               // floats per activation buffer
     constexpr int OBUF = T * S;                // floats of the output tile
-    constexpr bool DB = VEC && RS == 17;       // two activation buffers (multi-chunk layers)
-    constexpr int LDS_FLOATS = (DB ? 2 * XBUF : XBUF) > OBUF ? (DB ? 2 * XBUF : XBUF) : OBUF;
-    __shared__ __attribute__((aligned(16))) float lds[LDS_FLOATS];
+    constexpr bool DB = MULTI;                 // two activation buffers
+    __shared__ __attribute__((aligned(16))) float lds[XBUF > OBUF ? XBUF : OBUF];
+    __shared__ __attribute__((aligned(16))) float lds_b[DB ? XBUF : 4];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -134,59 +143,35 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
 #pragma unroll
             for (int a = 0; a < NA; ++a) acc[p][g][a] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    // ---- activation staging -------------------------------------------------
-    // VEC: a wave instruction moves 64 x 16 bytes from global memory to 1024
-    // contiguous LDS bytes.  The tile is T rows of RS slots (the last slot of a
-    // row is padding); slot g = row * RS + col.  Wave w issues instructions
-    // w, w+4, ... of the tile's T*RS/64.  Padding slots, rows past the last
-    // pixel and channels past c_in fetch some valid address instead: no entry
-    // ever reads those channels and a lane only ever reads its own pixel's row.
-    constexpr int NI = (T * RS / 64 + 3) / 4;          // instructions per wave
-    const float* xtile = x + pix0 * K;                      // uniform
-    const int rows_valid = (int)(M - pix0 < T ? M - pix0 : T);
-    uint32_t grow[VEC ? NI : 1];               // float offset of the slot's pixel row from xtile
-    int gcol[VEC ? NI : 1];                    // channel offset of the slot inside a chunk
-    if (VEC) {
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int g = ((i * 4 + wave) * 64 + lane) % (T * RS);
-            const int row = g / RS, col = g % RS;
-            grow[i] = (uint32_t)(row < rows_valid ? row : rows_valid - 1) * (uint32_t)K;
-            gcol[i] = (col < RS - 1 ? col : RS - 2) * 4;
-        }
-    }
-    auto issue_x_direct = [&](int c, float* buf) {
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            if ((i * 4 + wave) * 64 < T * RS) {
-                const int ch = min(c * KC + gcol[i], K - 4);      // keep the 16-byte read inside the row
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(xtile + (grow[i] + (uint32_t)ch)),
-                                                 (__attribute__((address_space(3))) void*)(buf + (i * 4 + wave) * 256),
-                                                 16, 0, 0);
-            }
-        }
-    };
-    // !VEC: registers, scalar loads, zero fill.
+    // ---- activation staging.  Thread t moves slots t, t+256, ... of the tile's
+    // T x (KC/4) 16-byte slots.  Rows past the last pixel repeat the last pixel
+    // (a lane only ever reads its own pixel's row); channels past c_in are never
+    // read by any entry (VEC) or are zero filled (!VEC).
     constexpr int C4 = KC / 4;
     constexpr int NL = T * C4 / 256;
-    v4f stage_reg[VEC ? 1 : NL];
-    auto issue_x_regs = [&](int c) {
+    const float* xtile = x + pix0 * K;
+    const int rows_valid = (int)(M - pix0 < T ? M - pix0 : T);
+    v4f stage_reg[NL];
+    auto issue_x = [&](int c) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int slot = i * 256 + threadIdx.x;
             const int row = slot / C4, col = (slot % C4) * 4;
-            const long long pix = pix0 + row;
-            const long long pixc = pix < M ? pix : M - 1;
-            v4f v;
-            for (int q = 0; q < 4; ++q) {
-                const int ch = c * KC + col + q;
-                const float t = x[pixc * K + (ch < K ? ch : 0)];
-                v[q] = (pix < M && ch < K) ? t : 0.f;
+            const float* rp = xtile + (size_t)(row < rows_valid ? row : rows_valid - 1) * K;
+            if (VEC) {
+                stage_reg[i] = *(const v4f*)(rp + min(c * KC + col, K - 4));
+            } else {
+                v4f v;
+                for (int q = 0; q < 4; ++q) {
+                    const int ch = c * KC + col + q;
+                    const float t = rp[ch < K ? ch : 0];
+                    v[q] = ch < K ? t : 0.f;
+                }
+                stage_reg[i] = v;
             }
-            stage_reg[i] = v;
         }
     };
-    auto write_x_regs = [&](float* buf) {
+    auto write_x = [&](float* buf) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int slot = i * 256 + threadIdx.x;
@@ -207,32 +192,15 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
         for (int q4 = 0; q4 < 4; ++q4) w[q4] = src[q4 * 64];
     };
 
-    v4f w_cur[4], w_nxt[4];
-    Record r_cur, r_nxt;
-    SBN_TS(0)
-    if (VEC) {
-        issue_x_direct(0, lds);
-    } else {
-        issue_x_regs(0);
-        write_x_regs(lds);
-    }
-    load_weights(0, w_cur);
-    r_cur = recs[0];
-    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wave's LDS-bound loads have landed
-    __syncthreads();
-    SBN_TS(1)
-
-    for (int c = 0; c < n_chunks; ++c) {
-        const float* xbuf = lds + (DB && (c & 1) ? XBUF : 0);
-        const bool more = c + 1 < n_chunks;
-        if (more) {                          // in flight while this chunk is multiplied
-            if (VEC) {
-                if (DB) issue_x_direct(c + 1, lds + ((c & 1) ? 0 : XBUF));
-            } else {
-                issue_x_regs(c + 1);
-            }
-            load_weights(c + 1, w_nxt);
-            r_nxt = recs[c + 1];
+    // One chunk: start the loads of the next chunk, multiply the current one out
+    // of `xbuf`, then store the arrived activations to `xnext` and synchronise.
+    auto chunk = [&](int c, const float* xbuf, float* xnext, const v4f (&w_cur)[4], v4f (&w_nxt)[4],
+                     const Record& r_cur, Record& r_nxt) {
+        if (MULTI) {                         // in flight while this chunk is multiplied
+            const int cn = c + 1 < n_chunks ? c + 1 : c;
+            issue_x(cn);
+            load_weights(cn, w_nxt);
+            r_nxt = recs[cn];
         }
         SBN_TS(2 + c * 4)
 
@@ -271,23 +239,28 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
         chunk_done:;
         }
         SBN_TS(3 + c * 4)
-        if (more) {
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) w_cur[q4] = w_nxt[q4];
-            r_cur = r_nxt;
-            if (!DB) {                       // single buffer: refill it once everybody has finished reading
-                __syncthreads();
-                if (VEC)
-                    issue_x_direct(c + 1, lds);
-                else
-                    write_x_regs(lds);
-            }
-        }
-        // every wave is done with this chunk's tile and its own loads of the next one have landed
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+        if (MULTI) write_x(xnext);
         SBN_TS(4 + c * 4)
-        __syncthreads();
+        __syncthreads();                     // tile of the next chunk published / this one released
         SBN_TS(5 + c * 4)
+    };
+
+    v4f w_a[4], w_b[4];
+    Record r_a, r_b;
+    SBN_TS(0)
+    issue_x(0);
+    load_weights(0, w_a);
+    r_a = recs[0];
+    write_x(lds);
+    __syncthreads();
+    SBN_TS(1)
+    if (MULTI) {
+        for (int c = 0; c < n_chunks; c += 2) {
+            chunk(c, lds, lds_b, w_a, w_b, r_a, r_b);
+            if (c + 1 < n_chunks) chunk(c + 1, lds_b, lds, w_b, w_a, r_b, r_a);
+        }
+    } else {
+        chunk(0, lds, lds, w_a, w_b, r_a, r_b);
     }
 
     // ---- epilogue: partial sums, bias, activation; transpose through LDS
@@ -324,7 +297,7 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
     SBN_TS(101)
 }
 
-template <int P, int NA, int RS, bool VEC>
+template <int P, int NA, int KC, bool MULTI, bool VEC>
 int launch(const sbn_packed* p, const float* x, float* y, long long M, hipStream_t st)
 {
     const sbn::DeviceLayout& L = p->dev;
@@ -332,7 +305,7 @@ int launch(const sbn_packed* p, const float* x, float* y, long long M, hipStream
     const int n_col_tiles = (L.n_bundles + 3) / 4;
     const long long grid = ((n_pix_tiles + 7) / 8) * 8 * n_col_tiles;
     if (grid > 0x7FFFFFFFll) return sbn::fail(SBN_EINVAL, "too many pixels for one launch (%lld)", M);
-    hipLaunchKernelGGL((conv1x1_kernel<P, NA, RS, VEC>), dim3((unsigned)grid), dim3(256), 0, st, x, y, L.d_records,
+    hipLaunchKernelGGL((conv1x1_kernel<P, NA, KC, MULTI, VEC>), dim3((unsigned)grid), dim3(256), 0, st, x, y, L.d_records,
                        L.d_woff, L.d_wts, L.d_bias, M, p->c_in, p->c_out, L.n_bundles, L.n_chunks, n_col_tiles,
                        (int)n_pix_tiles, p->act);
     hipError_t e = hipGetLastError();
@@ -347,25 +320,26 @@ namespace sbn {
 int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, void* stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    const bool vec = p->c_in % 4 == 0;
-    const bool k32 = p->c_in <= 32;
+    const int K = p->c_in;
     static const int force = getenv("SBN_K1_VARIANT") ? atoi(getenv("SBN_K1_VARIANT")) : 0;   // benchmarking override
-    if (!vec) return k32 ? launch<1, 2, 9, false>(p, x, y, M, st) : launch<1, 2, 17, false>(p, x, y, M, st);
-    if (k32) {
-        // one chunk, bound by HBM: 128 pixels per workgroup when there are plenty
-        const bool p2 = force ? force / 10 == 2 : M >= 128 * 1024;
-        return p2 ? launch<2, 1, 9, true>(p, x, y, M, st) : launch<1, 2, 9, true>(p, x, y, M, st);
+    if (K % 4) {
+        if (K <= 32) return launch<1, 2, 32, false, false>(p, x, y, M, st);
+        if (K <= 64) return launch<1, 2, 64, false, false>(p, x, y, M, st);
+        return launch<1, 2, 64, true, false>(p, x, y, M, st);
     }
+    // one chunk, bound by HBM: 128 pixels per workgroup when there are plenty
+    const bool p2 = force ? force / 10 == 2 : M >= 128 * 1024;
+    if (K <= 32) return p2 ? launch<2, 1, 32, false, true>(p, x, y, M, st) : launch<1, 2, 32, false, true>(p, x, y, M, st);
+    if (K <= 64) return p2 ? launch<2, 1, 64, false, true>(p, x, y, M, st) : launch<1, 2, 64, false, true>(p, x, y, M, st);
     switch (force) {
-    case 11: return launch<1, 1, 17, true>(p, x, y, M, st);
-    case 12: return launch<1, 2, 17, true>(p, x, y, M, st);
-    case 13: return launch<1, 3, 17, true>(p, x, y, M, st);
-    case 14: return launch<1, 4, 17, true>(p, x, y, M, st);
-    case 21: return launch<2, 1, 17, true>(p, x, y, M, st);
-    case 22: return launch<2, 2, 17, true>(p, x, y, M, st);
+    case 11: return launch<1, 1, 64, true, true>(p, x, y, M, st);
+    case 12: return launch<1, 2, 64, true, true>(p, x, y, M, st);
+    case 14: return launch<1, 4, 64, true, true>(p, x, y, M, st);
+    case 21: return launch<2, 1, 64, true, true>(p, x, y, M, st);
+    case 22: return launch<2, 2, 64, true, true>(p, x, y, M, st);
     default: break;
     }
-    return launch<1, 2, 17, true>(p, x, y, M, st);
+    return launch<1, 2, 64, true, true>(p, x, y, M, st);
 }
 
 }  // namespace sbn

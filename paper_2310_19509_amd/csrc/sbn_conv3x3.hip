@@ -4,12 +4,11 @@
 // Same engine as the 1x1 kernel, with every kept piece carrying nine taps.
 // One lane owns one output pixel of an 8x8 spatial tile; a wave owns one
 // bundle of four 4-filter groups; the four waves of a workgroup share the
-// input tile ((8-1)*stride+3)^2 pixels x 32 channels, staged in LDS straight
-// from global memory (global_load_lds_dwordx4, 9 slots of 16 bytes per pixel,
-// the ninth is padding).  Input positions outside the image fetch a block of
-// zeros instead, which realises the zero padding.  For stride 1 the tile is
-// double buffered so that the next 32 channels arrive while the current ones
-// are multiplied.
+// input tile ((8-1)*stride+3)^2 pixels x 32 channels, staged in LDS (pixel
+// stride 36 floats) through registers.  Input positions outside the image are
+// staged as zeros, which realises the zero padding.  For stride 1 the tile is
+// double buffered: the next 32 channels are fetched while the current ones are
+// multiplied and published with one barrier per sub-chunk.
 //
 // Per entry (a 4-channel piece kept by at least one group of the bundle) the
 // lane reads the nine shifted 16-byte activation vectors of its window, the
@@ -66,14 +65,13 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
     constexpr int IW = (TW - 1) * STRIDE + 3;          // input tile width
     constexpr int IH = (TH - 1) * STRIDE + 3;
     constexpr int NPIX = IW * IH;                      // staged input pixels
-    constexpr int NSLOT = NPIX * RS;
-    constexpr int NINST = (NSLOT + 63) / 64;           // wave instructions per staged tile
-    constexpr int NI = (NINST + 3) / 4;                // per wave
-    constexpr int XBUF = NINST * 256;                  // floats per activation buffer
+    constexpr int NSLOT = NPIX * (KC / 4);             // 16-byte slots of a staged tile
+    constexpr int NL = (NSLOT + 255) / 256;            // slots per thread
+    constexpr int XBUF = NPIX * XS;                    // floats per activation buffer
     constexpr bool DB = STRIDE == 1;
     constexpr int OBUF = 64 * OS;
-    constexpr int LDS_FLOATS = (DB ? 2 : 1) * XBUF > OBUF ? (DB ? 2 : 1) * XBUF : OBUF;
-    __shared__ __attribute__((aligned(16))) float lds[LDS_FLOATS];
+    __shared__ __attribute__((aligned(16))) float lds[XBUF > OBUF ? XBUF : OBUF];
+    __shared__ __attribute__((aligned(16))) float lds_b[DB ? XBUF : 4];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -96,31 +94,35 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
 #pragma unroll
     for (int g = 0; g < 4; ++g) acc[g][0] = acc[g][1] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    // ---- staging addresses.  Slot s = pixel * 9 + col; wave w issues instructions w, w+4, ...
+    // ---- staging: thread t moves slots t, t+256, ...; slot = pixel * 8 + col
     const float* xi = x + img * H * W * K;
-    const float* gpix[NI];        // channel 0 of the slot's input pixel (or the zero block)
-    int gcol[NI];                 // channel offset of the slot inside a 32-channel sub-chunk
-    bool ginside[NI];
+    const float* gpix[NL];        // channel 0 of the slot's input pixel (any valid address when outside)
+    int gcol[NL];
+    bool ginside[NL];
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        int s = (i * 4 + wave) * 64 + lane;
+    for (int i = 0; i < NL; ++i) {
+        int s = i * 256 + threadIdx.x;
         s = s < NSLOT ? s : NSLOT - 1;
-        const int pix = s / RS, col = s % RS;
+        const int pix = s / (KC / 4), col = s % (KC / 4);
         const int iy = iy0 + pix / IW, ix = ix0 + pix % IW;
         ginside[i] = iy >= 0 && iy < H && ix >= 0 && ix < W;
         gpix[i] = ginside[i] ? xi + ((long long)iy * W + ix) * K : zeros;
-        gcol[i] = (col < RS - 1 ? col : RS - 2) * 4;
+        gcol[i] = col * 4;
     }
-    auto issue_x = [&](int sc, float* buf) {
+    v4f stage_reg[NL];
+    auto issue_x = [&](int sc) {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            if (i * 4 + wave < NINST) {
-                // keep the 16-byte read inside the pixel's channels; outside the image read zeros
-                const int ch = ginside[i] ? min(gcol[i] + sc * KC, K - 4) : 0;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gpix[i] + ch),
-                                                 (__attribute__((address_space(3))) void*)(buf + (i * 4 + wave) * 256),
-                                                 16, 0, 0);
-            }
+        for (int i = 0; i < NL; ++i) {
+            // keep the 16-byte read inside the pixel's channels; outside the image read zeros
+            const int ch = ginside[i] ? min(gcol[i] + sc * KC, K - 4) : 0;
+            stage_reg[i] = *(const v4f*)(gpix[i] + ch);
+        }
+    };
+    auto write_x = [&](float* buf) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int s = i * 256 + threadIdx.x;
+            if (s < NSLOT) *(v4f*)(buf + (s / (KC / 4)) * XS + (s % (KC / 4)) * 4) = stage_reg[i];
         }
     };
 
@@ -132,16 +134,11 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
     const uint32_t* recs = records + (size_t)bsafe * n_chunks * 16;
     const int n_sub = (K + KC - 1) / KC;
 
-    issue_x(0, lds);
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-
     uint32_t dv = 0;          // descriptors of the current 64-channel record, one per lane (lanes 0..15)
     uint32_t q = 0, e = 0;
-    for (int sc = 0; sc < n_sub; ++sc) {
-        const float* xbuf = lds + (DB && (sc & 1) ? XBUF : 0);
-        const bool more = sc + 1 < n_sub;
-        if (more && DB) issue_x(sc + 1, lds + ((sc & 1) ? 0 : XBUF));
+    // One sub-chunk of 32 channels: fetch the next one, multiply this one, publish the next.
+    auto sub_chunk = [&](int sc, const float* xbuf, float* xnext) {
+        if (DB) issue_x(sc + 1 < n_sub ? sc + 1 : sc);      // unconditional: see the 1x1 kernel
         const uint32_t h = sc & 1;
         if (h == 0) {
             dv = recs[(sc >> 1) * 16 + (lane & 15)];
@@ -193,12 +190,20 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
                 }
             }
         }
-        if (more && !DB) {
-            __syncthreads();             // single buffer: everyone has finished reading it
-            issue_x(sc + 1, lds);
+        if (!DB) {                       // single buffer: fetch after everyone has finished reading it
+            __syncthreads();
+            issue_x(sc + 1 < n_sub ? sc + 1 : sc);
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+        write_x(xnext);
         __syncthreads();
+    };
+
+    issue_x(0);
+    write_x(lds);
+    __syncthreads();
+    for (int sc = 0; sc < n_sub; sc += 2) {
+        sub_chunk(sc, lds, DB ? lds_b : lds);
+        if (sc + 1 < n_sub) sub_chunk(sc + 1, DB ? lds_b : lds, lds);
     }
 
     // ---- epilogue: bias, activation, transpose through LDS, full 256-byte rows per pixel
