@@ -46,8 +46,6 @@ namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int S = 68;      // LDS row stride in floats (64 + 4 padding)
-
 template <int ABID>
 __device__ __forceinline__ v4f mfma_bcast(float w, float x, v4f c)
 {
@@ -85,8 +83,9 @@ __device__ __forceinline__ void entry_fma(uint32_t m, const v4f& w, const v4f (&
     if (__builtin_expect((m & 8u) != 0, 1)) group_fma<P, NA, Q, 3>(w, xv, acc);
 }
 
+template <int NS>
 struct Record {
-    uint32_t d[16];
+    uint32_t d[NS];
 };
 
 // P: pixel sets of 64 per wave.  NA: partial sums per (pixel set, group).
@@ -111,11 +110,12 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
                                                       int n_col_tiles, int n_pix_tiles, int act)
 {
     constexpr int T = 64 * P;                  // pixels per workgroup
+    constexpr int NS = KC / 4;                 // descriptors per record (one record per KC channels)
+    constexpr int NW = NS / 4;                 // 16-byte weight loads per lane and chunk
     constexpr int XS = KC + 4;                 // staged row stride in floats
     constexpr int XBUF = T * XS;               // floats per activation buffer
-    constexpr int OBUF = T * S;                // floats of the output tile
     constexpr bool DB = MULTI;                 // two activation buffers
-    __shared__ __attribute__((aligned(16))) float lds[XBUF > OBUF ? XBUF : OBUF];
+    __shared__ __attribute__((aligned(16))) float lds[XBUF];
     __shared__ __attribute__((aligned(16))) float lds_b[DB ? XBUF : 4];
 
     const int lane = threadIdx.x & 63;
@@ -180,22 +180,22 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
         }
     };
 
-    // ---- weights and descriptors of one chunk.  The four 16-byte loads cover
-    // 16 entries; entries past the chunk's own belong to later chunks or to the
+    // ---- weights and descriptors of one chunk.  NW 16-byte loads per lane cover
+    // NS entries; entries past the chunk's own belong to later chunks or to the
     // array's slack and are never used.
     const uint32_t* wo = woff + (size_t)bsafe * (n_chunks + 1);
-    const Record* recs = (const Record*)__builtin_assume_aligned(records, 64) + (size_t)bsafe * n_chunks;
-    auto load_weights = [&](int c, v4f (&w)[4]) {
+    const Record<NS>* recs = (const Record<NS>*)__builtin_assume_aligned(records, 4 * NS) + (size_t)bsafe * n_chunks;
+    auto load_weights = [&](int c, v4f (&w)[NW]) {
         const uint32_t e0 = __builtin_amdgcn_readfirstlane(wo[c]);
         const v4f* src = (const v4f*)(wts + (size_t)e0 * 64) + lane;
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) w[q4] = src[q4 * 64];
+        for (int q4 = 0; q4 < NW; ++q4) w[q4] = src[q4 * 64];
     };
 
     // One chunk: start the loads of the next chunk, multiply the current one out
     // of `xbuf`, then store the arrived activations to `xnext` and synchronise.
-    auto chunk = [&](int c, const float* xbuf, float* xnext, const v4f (&w_cur)[4], v4f (&w_nxt)[4],
-                     const Record& r_cur, Record& r_nxt) {
+    auto chunk = [&](int c, const float* xbuf, float* xnext, const v4f (&w_cur)[NW], v4f (&w_nxt)[NW],
+                     const Record<NS>& r_cur, Record<NS>& r_nxt) {
         if (MULTI) {                         // in flight while this chunk is multiplied
             const int cn = c + 1 < n_chunks ? c + 1 : c;
             issue_x(cn);
@@ -215,9 +215,11 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
             // Entries are compacted at the front of the record; the first zero
             // descriptor ends the chunk.  Activations run one entry ahead.
 #define SBN_ENTRY(Q, XC, XN)                                                   \
-    if (__builtin_expect(r_cur.d[Q] == 0, 0)) goto chunk_done;                 \
-    if (Q + 1 < 16) read_x(r_cur.d[(Q + 1) & 15], XN);                         \
-    entry_fma<P, NA, Q>(r_cur.d[Q], w_cur[(Q) >> 2], XC, acc);
+    if (Q < NS) {                                                              \
+        if (__builtin_expect(r_cur.d[Q % NS] == 0, 0)) goto chunk_done;        \
+        if (Q + 1 < NS) read_x(r_cur.d[(Q + 1) % NS], XN);                     \
+        entry_fma<P, NA, Q>(r_cur.d[Q % NS], w_cur[(Q / 4) % NW], XC, acc);    \
+    }
             read_x(r_cur.d[0], xa);
             SBN_ENTRY(0, xa, xb)
             SBN_ENTRY(1, xb, xa)
@@ -245,8 +247,8 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
         SBN_TS(5 + c * 4)
     };
 
-    v4f w_a[4], w_b[4];
-    Record r_a, r_b;
+    v4f w_a[NW], w_b[NW];
+    Record<NS> r_a, r_b;
     SBN_TS(0)
     issue_x(0);
     load_weights(0, w_a);
@@ -263,36 +265,42 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
         chunk(0, lds, lds, w_a, w_b, r_a, r_b);
     }
 
-    // ---- epilogue: partial sums, bias, activation; transpose through LDS
-    // (the barrier that ended the last chunk makes the tile memory reusable)
-    if (active) {
+    // ---- epilogue: partial sums, bias, activation; the output tile is transposed
+    // through LDS in passes of KC channels (KC/16 waves each) and stored as full rows.
+    // (The barrier that ended the last chunk makes the tile memory reusable.)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const v4f b = *(const v4f*)(bias + bundle * 16 + g * 4);
+    for (int h = 0; h < 64 / KC; ++h) {
+        if (h) __syncthreads();
+        if (active && wave / (KC / 16) == h) {
 #pragma unroll
-            for (int p = 0; p < P; ++p) {
-                v4f o = acc[p][g][0];
+            for (int g = 0; g < 4; ++g) {
+                const v4f b = *(const v4f*)(bias + bundle * 16 + g * 4);
 #pragma unroll
-                for (int a = 1; a < NA; ++a) o += acc[p][g][a];
-                o += b;
-                if (act == SBN_ACT_RELU) {
-                    o.x = fmaxf(o.x, 0.f);
-                    o.y = fmaxf(o.y, 0.f);
-                    o.z = fmaxf(o.z, 0.f);
-                    o.w = fmaxf(o.w, 0.f);
+                for (int p = 0; p < P; ++p) {
+                    v4f o = acc[p][g][0];
+#pragma unroll
+                    for (int a = 1; a < NA; ++a) o += acc[p][g][a];
+                    o += b;
+                    if (act == SBN_ACT_RELU) {
+                        o.x = fmaxf(o.x, 0.f);
+                        o.y = fmaxf(o.y, 0.f);
+                        o.z = fmaxf(o.z, 0.f);
+                        o.w = fmaxf(o.w, 0.f);
+                    }
+                    *(v4f*)(lds + (p * 64 + lane) * XS + (wave % (KC / 16)) * 16 + g * 4) = o;
                 }
-                *(v4f*)(lds + (p * 64 + lane) * S + wave * 16 + g * 4) = o;
             }
         }
-    }
-    __syncthreads();
-    const int ch_base = col_tile * 64;
+        __syncthreads();
+        const int ch_base = col_tile * 64 + h * KC;
 #pragma unroll
-    for (int i = 0; i < T * 16 / 256; ++i) {
-        const int slot = i * 256 + threadIdx.x;
-        const int row = slot >> 4, col = (slot & 15) * 4;
-        const long long pix = pix0 + row;
-        if (pix < M && ch_base + col < N) *(v4f*)(y + pix * N + ch_base + col) = *(const v4f*)(lds + row * S + col);
+        for (int i = 0; i < NL; ++i) {
+            const int slot = i * 256 + threadIdx.x;
+            const int row = slot / C4, col = (slot % C4) * 4;
+            const long long pix = pix0 + row;
+            if (pix < M && ch_base + col < N)
+                *(v4f*)(y + pix * N + ch_base + col) = *(const v4f*)(lds + row * XS + col);
+        }
     }
     SBN_TS(101)
 }
@@ -305,8 +313,9 @@ int launch(const sbn_packed* p, const float* x, float* y, long long M, hipStream
     const int n_col_tiles = (L.n_bundles + 3) / 4;
     const long long grid = ((n_pix_tiles + 7) / 8) * 8 * n_col_tiles;
     if (grid > 0x7FFFFFFFll) return sbn::fail(SBN_EINVAL, "too many pixels for one launch (%lld)", M);
-    hipLaunchKernelGGL((conv1x1_kernel<P, NA, KC, MULTI, VEC>), dim3((unsigned)grid), dim3(256), 0, st, x, y, L.d_records,
-                       L.d_woff, L.d_wts, L.d_bias, M, p->c_in, p->c_out, L.n_bundles, L.n_chunks, n_col_tiles,
+    hipLaunchKernelGGL((conv1x1_kernel<P, NA, KC, MULTI, VEC>), dim3((unsigned)grid), dim3(256), 0, st, x, y,
+                       KC == 64 ? L.d_records : L.d_records32, KC == 64 ? L.d_woff : L.d_woff32, L.d_wts, L.d_bias, M,
+                       p->c_in, p->c_out, L.n_bundles, KC == 64 ? L.n_chunks : L.n_chunks32, n_col_tiles,
                        (int)n_pix_tiles, p->act);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return sbn::fail(SBN_EHIP, "conv1x1 launch: %s", hipGetErrorString(e));
@@ -331,15 +340,20 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
     const bool p2 = force ? force / 10 == 2 : M >= 128 * 1024;
     if (K <= 32) return p2 ? launch<2, 1, 32, false, true>(p, x, y, M, st) : launch<1, 2, 32, false, true>(p, x, y, M, st);
     if (K <= 64) return p2 ? launch<2, 1, 64, false, true>(p, x, y, M, st) : launch<1, 2, 64, false, true>(p, x, y, M, st);
-    switch (force) {
-    case 11: return launch<1, 1, 64, true, true>(p, x, y, M, st);
-    case 12: return launch<1, 2, 64, true, true>(p, x, y, M, st);
-    case 14: return launch<1, 4, 64, true, true>(p, x, y, M, st);
-    case 21: return launch<2, 1, 64, true, true>(p, x, y, M, st);
-    case 22: return launch<2, 2, 64, true, true>(p, x, y, M, st);
-    default: break;
+    int variant = force;
+    if (!variant) {
+        // 128-pixel tiles with 32-channel chunks halve the per-entry overhead; they pay off
+        // when there are still several such tiles per CU (256 CUs)
+        const int n_col_tiles = (p->dev.n_bundles + 3) / 4;
+        variant = ((M + 127) / 128) * n_col_tiles >= 6 * 256 ? 21 : 12;
     }
-    return launch<1, 2, 64, true, true>(p, x, y, M, st);
+    switch (variant) {
+    case 11: return launch<1, 1, 64, true, true>(p, x, y, M, st);
+    case 14: return launch<1, 4, 64, true, true>(p, x, y, M, st);
+    case 21: return launch<2, 1, 32, true, true>(p, x, y, M, st);
+    case 22: return launch<2, 2, 32, true, true>(p, x, y, M, st);
+    default: return launch<1, 2, 64, true, true>(p, x, y, M, st);
+    }
 }
 
 }  // namespace sbn

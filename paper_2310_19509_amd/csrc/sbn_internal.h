@@ -42,15 +42,20 @@ struct DeviceLayout {
     int n_bundles = 0;
     int n_chunks = 0;                     // ceil(c_in / 64)
     size_t n_entries = 0;
+    int n_chunks32 = 0;                   // ceil(c_in / 32)
     // host staging
     std::vector<uint32_t> records;        // [n_bundles][n_chunks][16]
     std::vector<uint32_t> woff;           // [n_bundles][n_chunks + 1]
+    std::vector<uint32_t> records32;      // [n_bundles][n_chunks32][8]: the same entries per 32 channels,
+    std::vector<uint32_t> woff32;         // [n_bundles][n_chunks32 + 1]   kb4_in_chunk < 8
     std::vector<float> wts;
     std::vector<float> bias_padded;       // [n_bundles * 16], zeros when no bias
     // device copies (one allocation)
     void* d_blob = nullptr;
     uint32_t* d_records = nullptr;
     uint32_t* d_woff = nullptr;
+    uint32_t* d_records32 = nullptr;
+    uint32_t* d_woff32 = nullptr;
     float* d_wts = nullptr;
     float* d_bias = nullptr;
     float* d_zeros = nullptr;             // 64 zero floats (source of out-of-image activation slots)

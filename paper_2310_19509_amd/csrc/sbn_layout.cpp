@@ -22,8 +22,11 @@ void build_device_layout(sbn_packed* p)
     const size_t wstride = (size_t)taps * kBundleGroups * 16;        // floats per entry
     const size_t blk = (size_t)taps * gi * go;
 
+    L.n_chunks32 = (p->c_in + 31) / 32;
     L.records.assign((size_t)L.n_bundles * L.n_chunks * kSlots, 0u);
     L.woff.assign((size_t)L.n_bundles * (L.n_chunks + 1), 0u);
+    L.records32.assign((size_t)L.n_bundles * L.n_chunks32 * 8, 0u);
+    L.woff32.assign((size_t)L.n_bundles * (L.n_chunks32 + 1), 0u);
     L.wts.clear();
     size_t n_entries = 0;
 
@@ -66,6 +69,16 @@ void build_device_layout(sbn_packed* p)
         }
         // empty chunks start where the next non-empty one does
         for (int c = L.n_chunks - 1; c >= 0; --c) wo[c] = std::min(wo[c], wo[c + 1]);
+        // the same entries, one record of 8 descriptors per 32 channels
+        uint32_t* wo32 = &L.woff32[(size_t)b * (L.n_chunks32 + 1)];
+        std::vector<int> fill32((size_t)L.n_chunks32, 0);
+        for (int c = 0; c <= L.n_chunks32; ++c) wo32[c] = (uint32_t)n_entries;
+        for (const auto& kv : pos) {
+            const int c = kv.first / 8, q = fill32[(size_t)c]++;
+            L.records32[((size_t)b * L.n_chunks32 + c) * 8 + q] = ((uint32_t)(kv.first % 8) << 8) | kv.second.second;
+            wo32[c] = std::min(wo32[c], (uint32_t)kv.second.first);
+        }
+        for (int c = L.n_chunks32 - 1; c >= 0; --c) wo32[c] = std::min(wo32[c], wo32[c + 1]);
         (void)first;
     }
     L.n_entries = n_entries;
@@ -91,9 +104,11 @@ int upload_device_layout(sbn_packed* p)
     const size_t wstride = (size_t)p->kh * p->kw * kBundleGroups * 16;
     const size_t b_rec = align256(L.records.size() * sizeof(uint32_t));
     const size_t b_woff = align256(L.woff.size() * sizeof(uint32_t));
+    const size_t b_rec32 = align256(L.records32.size() * sizeof(uint32_t));
+    const size_t b_woff32 = align256(L.woff32.size() * sizeof(uint32_t));
     const size_t b_wts = align256((L.wts.size() + kSlots * wstride) * sizeof(float));
     const size_t b_bias = align256((L.bias_padded.size() + 64) * sizeof(float));   // + a block of zeros
-    const size_t total = b_rec + b_woff + b_wts + b_bias;
+    const size_t total = b_rec + b_woff + b_rec32 + b_woff32 + b_wts + b_bias;
     char* blob = nullptr;
     if ((e = hipMalloc((void**)&blob, total)) != hipSuccess) {
         (void)hipSetDevice(prev);
@@ -107,6 +122,12 @@ int upload_device_layout(sbn_packed* p)
     std::memcpy(host.data() + off, L.woff.data(), L.woff.size() * sizeof(uint32_t));
     L.d_woff = (uint32_t*)(blob + off);
     off += b_woff;
+    std::memcpy(host.data() + off, L.records32.data(), L.records32.size() * sizeof(uint32_t));
+    L.d_records32 = (uint32_t*)(blob + off);
+    off += b_rec32;
+    std::memcpy(host.data() + off, L.woff32.data(), L.woff32.size() * sizeof(uint32_t));
+    L.d_woff32 = (uint32_t*)(blob + off);
+    off += b_woff32;
     std::memcpy(host.data() + off, L.wts.data(), L.wts.size() * sizeof(float));
     L.d_wts = (float*)(blob + off);
     off += b_wts;
