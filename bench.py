@@ -25,6 +25,9 @@ PEAK_HBM_GBS = 8000.0             # MI355X published HBM3E bandwidth
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--workload", default="pw13", choices=["pw13", "mobilenet", "conv3x3"],
+                    help="pw13: the 13 pointwise layers (headline metric); mobilenet: the whole network as one "
+                         "chain, batch 64, 50 %% sparsity; conv3x3: ResNet-50-shaped 3x3 layers, batch 32, 70 %%")
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--batch", type=int, default=64)
@@ -60,6 +63,43 @@ def build_layers(S, W, batch, pct, go, rearrange):
     return tens, perms, packed, (time.perf_counter() - t0) * 1e3
 
 
+def build_mobilenet_chain(S, W, pct, go=4, seed=4000, max_iters=300):
+    """Config 4: the whole MobileNet-v1 as one chain.  Pointwise layers are rearranged over
+    the whole network (a layer's filter order is the next layer's channel order; the depthwise
+    layers in between follow it), pruned by block magnitude and packed; stem, depthwise layers
+    and the classifier stay dense.  Returns (chain, meta) where meta describes every item for
+    the oracle."""
+    import numpy as np
+    t = W.mobilenet_v1_tensors(seed)
+    n = len(t["pw"])
+    descs = [dict(kind=S.SBN_CONV1X1, w=l["w"], go=go, gi=4) for l in t["pw"]]
+    descs.append(dict(kind=S.SBN_CONV1X1, w=t["fc"]["w"], go=4, gi=4))
+    # the classifier absorbs the last pointwise layer's order; its own output order is kept
+    perms = S.sbn_rearrange(descs, [-1] + list(range(n)), pct, seed=seed, max_iters=max_iters,
+                            keep_output_order=[0] * n + [1])
+    items = [S.stem_item(t["stem"]["w"], t["stem"]["bias"], stride=W.STEM["stride"], act=S.SBN_ACT_RELU)]
+    meta = [dict(kind="stem", w=t["stem"]["w"], b=t["stem"]["bias"], stride=W.STEM["stride"])]
+    pin = None
+    for i in range(n):
+        d = W.MOBILENET_V1_DW[i]
+        items.append(S.dw_item(t["dw"][i]["w"], t["dw"][i]["bias"], stride=d.stride, act=S.SBN_ACT_RELU))
+        meta.append(dict(kind="dw", w=t["dw"][i]["w"], b=t["dw"][i]["bias"], stride=d.stride, order=pin))
+        w, b = t["pw"][i]["w"], t["pw"][i]["bias"]
+        wp = w[perms[i]] if pin is None else w[perms[i]][..., pin]
+        mask = S.sbn_prune_magnitude(np.ascontiguousarray(wp), S.SBN_CONV1X1, go, 4, pct)
+        p = S.sbn_pack(S.SBN_CONV1X1, w, go, 4, mask=mask, bias=b, perm_out=perms[i], perm_in=pin, act=S.SBN_ACT_RELU,
+                       device=0)
+        items.append(S.sparse_item(p))
+        meta.append(dict(kind="pw", w=w, b=b, mask=mask, po=perms[i], pi=pin, go=go, act=1))
+        pin = perms[i]
+    items.append(S.avgpool_item())
+    meta.append(dict(kind="pool"))
+    fc = S.sbn_pack(S.SBN_CONV1X1, t["fc"]["w"], 4, 4, bias=t["fc"]["bias"], perm_in=pin, device=0)
+    items.append(S.sparse_item(fc))
+    meta.append(dict(kind="pw", w=t["fc"]["w"], b=t["fc"]["bias"], mask=None, po=None, pi=pin, go=4, act=0))
+    return S.sbn_chain_create(items), meta
+
+
 def cpu_baseline(W, tens, perms, pct, go, batch):
     """The parity oracle (dense direct conv on masked weights, fp64, OpenMP) on a batch slice."""
     import numpy as np
@@ -92,6 +132,115 @@ def cpu_baseline(W, tens, perms, pct, go, batch):
                        f"threads; nonzero FLOPs counted, the oracle itself multiplies every (zeroed) weight in fp64")
 
 
+def time_steps(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def run_mobilenet(a, torch, S, W):
+    """Config 4: whole MobileNet-v1 forward as one chain on one stream (layers depend on each other)."""
+    B, pct = a.batch, 50 if a.sparsity == 30 else a.sparsity
+    t0 = time.perf_counter()
+    chain, meta = build_mobilenet_chain(S, W, pct, go=a.go)
+    pack_ms = (time.perf_counter() - t0) * 1e3
+    hw = W.STEM["hw_in"]
+    g = torch.Generator(device="cuda").manual_seed(4000)
+    x = torch.rand((B, hw, hw, 3), device="cuda", generator=g) * 2 - 1
+    y = torch.empty((B, 1, 1, 1000), device="cuda")
+    ws = torch.empty(S.sbn_chain_workspace(chain, B, hw, hw) // 4, device="cuda")
+    ms = time_steps(torch, lambda: S.sbn_pointwise_chain(chain, x, y, B, hw, hw, ws), a.steps, a.warmup)
+    macs = W.mobilenet_v1_macs()
+    nz = 0.0
+    for m, L in zip([m for m in meta if m["kind"] == "pw"][:13], W.MOBILENET_V1_PW):
+        nz += 2.0 * int(m["mask"].sum()) * a.go * 4 * B * L.hw * L.hw
+    dense_rest = 2.0 * B * (macs["stem"] + macs["dw"] + macs["fc"])
+    act_bytes = 4.0 * B * (hw * hw * 3 + 2 * sum(d.hw_out ** 2 * d.c for d in W.MOBILENET_V1_DW)
+                           + W.STEM["hw_out"] ** 2 * W.STEM["c_out"]
+                           + sum(p.hw ** 2 * (p.c_in + p.c_out) for p in W.MOBILENET_V1_PW))
+    t_roof = nz / (PEAK_MFMA_F32_TFLOPS * 1e12)
+    out = {
+        "metric": "effective GFLOP/s (nonzero FLOPs), whole MobileNet-v1 forward", "value": round((nz + dense_rest) / (ms * 1e-3) / 1e9, 1),
+        "unit": "GFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"MobileNet-v1 forward, batch {B}, 224x224x3 fp32, sparse pointwise layers "
+                               f"({pct}% group sparsity, go={a.go} gi=4, rearranged) chained with dense stem, "
+                               f"depthwise 3x3 + ReLU, average pool and classifier", "batch": B,
+                   "sparsity_percent": pct},
+        "roofline": {"bound": "hbm", "achieved": round(act_bytes / (ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": round(act_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None,
+                     "kernel": "whole chain (29 launches); activation bytes of every layer read and written once"},
+        "extra": {"images_per_s": round(B / (ms * 1e-3), 1), "offline_pack_ms": round(pack_ms, 1),
+                  "pointwise_nonzero_gflop": round(nz / 1e9, 2), "dense_rest_gflop": round(dense_rest / 1e9, 2),
+                  "pointwise_mfma_roof_ms": round(t_roof * 1e3, 4),
+                  "paper_context": "Snapdragon 855: 32.22 ms dense, 19.68 ms at 50% per image (batch 1)"},
+    }
+    print(json.dumps(out))
+
+
+def run_conv3x3(a, torch, S, W):
+    """Config 5: ResNet-50-shaped 3x3 layers, batch 32, kernel-level group sparsity 70 %."""
+    B, pct = 32 if a.batch == 64 else a.batch, 70 if a.sparsity == 30 else a.sparsity
+    layers, flops, xs, ys, hws = [], [], [], [], []
+    for idx in range(len(W.RESNET50_3X3)):
+        t = W.conv3x3_layer_tensors(5000, idx, B, with_x=False)
+        mask = S.sbn_prune_magnitude(t["w"], S.SBN_CONV3X3, a.go, 4, pct)
+        p = S.sbn_pack(S.SBN_CONV3X3, t["w"], a.go, 4, mask=mask, bias=t["bias"], act=S.SBN_ACT_RELU, device=0)
+        layers.append(p)
+        hws.append(t["hw"])
+        xs.append(torch.rand((B, t["hw"], t["hw"], t["c"]), device="cuda") * 2 - 1)
+        ys.append(torch.empty((B, t["hw"], t["hw"], t["c"]), device="cuda"))
+        flops.append(2.0 * S.sbn_packed_work(p)["macs_per_pixel"] * B * t["hw"] ** 2)
+    side = [torch.cuda.Stream() for _ in range(max(1, a.streams))]
+
+    def step():
+        for i, p in enumerate(layers):
+            S.sbn_conv3x3_sparse(p, xs[i], ys[i], B, hws[i], hws[i], stream=side[i % len(side)])
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    main = torch.cuda.current_stream()
+    e0.record(main)
+    for st in side:
+        st.wait_event(e0)
+    for _ in range(a.steps):
+        step()
+    for st in side:
+        ev = torch.cuda.Event()
+        ev.record(st)
+        main.wait_event(ev)
+    e1.record(main)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / a.steps
+    per = []
+    for i, p in enumerate(layers):
+        t = time_steps(torch, lambda: S.sbn_conv3x3_sparse(p, xs[i], ys[i], B, hws[i], hws[i]), 50, 10) * 1e-3
+        per.append(dict(c=W.RESNET50_3X3[i][0], hw=hws[i], us=round(t * 1e6, 1), tflops=round(flops[i] / t / 1e12, 2)))
+    ach = sum(flops) / len(layers) / (ms * 1e-3 / len(layers)) / 1e12
+    out = {
+        "metric": "effective GFLOP/s (nonzero FLOPs), ResNet-50-shaped 3x3 layers", "value": round(sum(flops) / (ms * 1e-3) / 1e9, 1),
+        "unit": "GFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"4 ResNet-50-shaped 3x3 convs (C 64..512, spatial 56..7), batch {B}, fp32, "
+                               f"kernel-level group sparsity {pct}% (go={a.go} gi=4 whole kernels)", "batch": B,
+                   "sparsity_percent": pct},
+        "roofline": {"bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(ach / PEAK_MFMA_F32_TFLOPS, 4), "traffic": None,
+                     "kernel": "conv3x3_kernel<1> (4 launches per step)"},
+        "extra": {"streams": len(side), "per_layer": per},
+    }
+    print(json.dumps(out))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -103,6 +252,10 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if a.workload == "mobilenet":
+        return run_mobilenet(a, torch, S, W)
+    if a.workload == "conv3x3":
+        return run_conv3x3(a, torch, S, W)
     B = a.batch
     tens, perms, packed, pack_ms = build_layers(S, W, B, a.sparsity, a.go, not a.no_rearrange)
     dense = [] if a.no_dense else [S.sbn_pack(S.SBN_CONV1X1, t["w"], a.go, 4, bias=t["bias"], act=S.SBN_ACT_RELU,

@@ -191,15 +191,19 @@ int sbn_conv3x3_sparse(const sbn_packed_t* p, const float* x, float* y,
 #define SBN_ITEM_SPARSE  1   /* a packed 1x1 or 3x3 layer                                 */
 #define SBN_ITEM_DW3X3   2   /* dense depthwise 3x3, pad 1, + bias + act                  */
 #define SBN_ITEM_AVGPOOL 3   /* global average over h*w -> 1x1 spatial                    */
+#define SBN_ITEM_STEM3X3 4   /* dense 3x3 conv of a few input channels (network stem),
+                                pad 1, + bias + act; only as the first item of a chain    */
 
 typedef struct {
     int item;                   /* SBN_ITEM_*                                              */
     const sbn_packed_t* packed; /* SBN_ITEM_SPARSE: the layer (borrowed)                   */
-    int channels;               /* SBN_ITEM_DW3X3: channel count                            */
-    int stride;                 /* SBN_ITEM_DW3X3: 1 or 2                                   */
-    int act;                    /* SBN_ITEM_DW3X3: SBN_ACT_*                                */
-    const float* dw_w;          /* SBN_ITEM_DW3X3: host [channels][3][3], ORIGINAL order    */
-    const float* dw_bias;       /* SBN_ITEM_DW3X3: host [channels] original order or NULL   */
+    int channels;               /* SBN_ITEM_DW3X3: channel count; SBN_ITEM_STEM3X3: c_in (1..4) */
+    int stride;                 /* SBN_ITEM_DW3X3 / SBN_ITEM_STEM3X3: 1 or 2                */
+    int act;                    /* SBN_ITEM_DW3X3 / SBN_ITEM_STEM3X3: SBN_ACT_*             */
+    const float* dw_w;          /* SBN_ITEM_DW3X3: host [channels][3][3], ORIGINAL order;
+                                   SBN_ITEM_STEM3X3: host OHWI [c_out][3][3][c_in]          */
+    const float* dw_bias;       /* host [channels] (DW3X3) / [c_out] (STEM3X3) or NULL      */
+    int c_out;                  /* SBN_ITEM_STEM3X3: output channels, multiple of 4, <= 64  */
 } sbn_chain_item_t;
 
 /*

@@ -45,7 +45,7 @@ class LayerDesc(C.Structure):
 
 class ChainItem(C.Structure):
     _fields_ = [("item", C.c_int), ("packed", C.c_void_p), ("channels", C.c_int), ("stride", C.c_int),
-                ("act", C.c_int), ("dw_w", C.c_void_p), ("dw_bias", C.c_void_p)]
+                ("act", C.c_int), ("dw_w", C.c_void_p), ("dw_bias", C.c_void_p), ("c_out", C.c_int)]
 
 
 # name -> (restype, argtypes): every symbol include/sbn.h declares

@@ -15,12 +15,12 @@ __all__ = [
     "sbn_last_error", "sbn_prune_magnitude", "sbn_retained_l1", "sbn_rearrange", "sbn_pack", "sbn_unpack",
     "sbn_export", "sbn_packed_info", "sbn_packed_work", "sbn_free", "sbn_conv1x1_sparse", "sbn_conv3x3_sparse",
     "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_chain_free",
-    "sbn_copy_bytes", "dw_item", "sparse_item", "avgpool_item",
+    "sbn_copy_bytes", "dw_item", "sparse_item", "avgpool_item", "stem_item", "SBN_ITEM_STEM3X3",
 ]
 
 SBN_CONV1X1, SBN_CONV3X3 = 1, 3
 SBN_ACT_NONE, SBN_ACT_RELU = 0, 1
-SBN_ITEM_SPARSE, SBN_ITEM_DW3X3, SBN_ITEM_AVGPOOL = 1, 2, 3
+SBN_ITEM_SPARSE, SBN_ITEM_DW3X3, SBN_ITEM_AVGPOOL, SBN_ITEM_STEM3X3 = 1, 2, 3, 4
 
 
 class SbnError(RuntimeError):
@@ -221,6 +221,11 @@ def dw_item(w, bias=None, stride: int = 1, act: int = SBN_ACT_RELU) -> dict:
     return dict(item=SBN_ITEM_DW3X3, w=_f32(w), bias=None if bias is None else _f32(bias), stride=stride, act=act)
 
 
+def stem_item(w_ohwi, bias=None, stride: int = 2, act: int = SBN_ACT_RELU) -> dict:
+    w = _f32(w_ohwi)
+    return dict(item=SBN_ITEM_STEM3X3, w=w, bias=None if bias is None else _f32(bias), stride=stride, act=act)
+
+
 def avgpool_item() -> dict:
     return dict(item=SBN_ITEM_AVGPOOL)
 
@@ -234,6 +239,14 @@ def sbn_chain_create(items: Sequence[dict], device: int = 0) -> Chain:
         if it["item"] == SBN_ITEM_SPARSE:
             arr[i].packed = it["packed"].handle
             keep.append(it["packed"])
+        elif it["item"] == SBN_ITEM_STEM3X3:
+            arr[i].channels = it["w"].shape[3]
+            arr[i].c_out = it["w"].shape[0]
+            arr[i].stride = it["stride"]
+            arr[i].act = it["act"]
+            arr[i].dw_w = it["w"].ctypes.data
+            arr[i].dw_bias = _ptr(it["bias"])
+            keep.append(it)
         elif it["item"] == SBN_ITEM_DW3X3:
             arr[i].channels = it["w"].shape[0]
             arr[i].stride = it["stride"]

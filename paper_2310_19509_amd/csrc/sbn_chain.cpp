@@ -14,7 +14,7 @@ struct sbn_chain {
     struct Item {
         int item = 0;
         const sbn_packed* packed = nullptr;
-        int channels = 0, stride = 1, act = 0;
+        int channels = 0, stride = 1, act = 0, c_out = 0;
         float* d_w = nullptr;      // depthwise: [9][channels] in the arriving channel order
         float* d_b = nullptr;      // depthwise: [channels]
     };
@@ -48,6 +48,11 @@ Shape next_shape(const sbn_chain::Item& it, Shape s)
         break;
     case SBN_ITEM_AVGPOOL:
         s.h = s.w = 1;
+        break;
+    case SBN_ITEM_STEM3X3:
+        s.h = (s.h - 1) / it.stride + 1;
+        s.w = (s.w - 1) / it.stride + 1;
+        s.c = it.c_out;
         break;
     }
     return s;
@@ -116,6 +121,20 @@ int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn
             it.act = s.act;
             cur_c = s.channels;
             dw_floats += (size_t)10 * s.channels;
+        } else if (s.item == SBN_ITEM_STEM3X3) {
+            if (i != 0) { delete c; return fail(SBN_ESHAPE, "the stem convolution must be the first item of a chain"); }
+            if (s.channels < 1 || s.channels > 4 || s.c_out <= 0 || s.c_out % 4 || s.c_out > 64 || !s.dw_w ||
+                (s.stride != 1 && s.stride != 2) || (s.act != SBN_ACT_NONE && s.act != SBN_ACT_RELU)) {
+                delete c;
+                return fail(SBN_EINVAL, "chain item %d: bad stem description (c_in 1..4, c_out multiple of 4 and <= 64, stride 1 or 2)", i);
+            }
+            c->c_in = s.channels;
+            it.channels = s.channels;
+            it.c_out = s.c_out;
+            it.stride = s.stride;
+            it.act = s.act;
+            cur_c = s.c_out;
+            dw_floats += (size_t)s.c_out * (9 * s.channels + 1);
         } else if (s.item == SBN_ITEM_AVGPOOL) {
             if (cur_c < 0) { delete c; return fail(SBN_ESHAPE, "a chain cannot start with the average pool"); }
             it.channels = cur_c;
@@ -143,6 +162,20 @@ int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn
         for (int i = 0; i < n_items; ++i) {
             sbn_chain::Item& it = c->items[(size_t)i];
             if (it.item == SBN_ITEM_SPARSE) ord = it.packed->perm_out;
+            if (it.item == SBN_ITEM_STEM3X3) {
+                // [tap][ci][c_out] and bias, original order (nothing precedes the stem)
+                const int ci_n = it.channels, co_n = it.c_out;
+                for (int o = 0; o < co_n; ++o) {
+                    for (int t = 0; t < 9; ++t)
+                        for (int ci = 0; ci < ci_n; ++ci)
+                            host[off + ((size_t)t * ci_n + ci) * co_n + o] = items[i].dw_w[((size_t)o * 9 + t) * ci_n + ci];
+                    host[off + (size_t)9 * ci_n * co_n + o] = items[i].dw_bias ? items[i].dw_bias[o] : 0.0f;
+                }
+                it.d_w = blob + off;
+                it.d_b = blob + off + (size_t)9 * ci_n * co_n;
+                off += (size_t)co_n * (9 * ci_n + 1);
+                continue;
+            }
             if (it.item != SBN_ITEM_DW3X3) continue;
             const int ch_n = it.channels;
             for (int ch = 0; ch < ch_n; ++ch) {
@@ -227,6 +260,10 @@ int sbn_pointwise_chain(const sbn_chain_t* c, const float* x, float* y, int n, i
             break;
         case SBN_ITEM_AVGPOOL:
             rc = launch_avgpool(src, dst, (int)s.n, s.h * s.w, s.c, stream);
+            break;
+        case SBN_ITEM_STEM3X3:
+            rc = launch_stem3x3(src, dst, it.d_w, it.d_b, (int)s.n, s.h, s.w, it.channels, it.c_out, it.stride, it.act,
+                                stream);
             break;
         }
         if (rc) return rc;

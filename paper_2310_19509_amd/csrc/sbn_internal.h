@@ -91,6 +91,8 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long m, v
 int launch_conv3x3(const sbn_packed* p, const float* x, float* y, int n, int h, int w, void* stream);
 int launch_dw3x3(const float* x, float* y, const float* w_dev, const float* b_dev, int n, int h, int w,
                  int c, int stride, int act, void* stream);
+int launch_stem3x3(const float* x, float* y, const float* w_dev, const float* b_dev, int n, int h, int w, int c_in,
+                   int c_out, int stride, int act, void* stream);
 int launch_avgpool(const float* x, float* y, int n, int hw, int c, void* stream);
 int launch_copy(const void* src, void* dst, size_t bytes, void* stream);
 

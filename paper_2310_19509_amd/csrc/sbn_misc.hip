@@ -15,22 +15,95 @@ __global__ __launch_bounds__(256) void copy_kernel(const v4f* __restrict__ src, 
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
-// One thread: 4 channels of one output pixel.  x [n][h][w][c], wt [9][c], y [n][oh][ow][c].
+// Dense depthwise 3x3, pad 1.  One thread: 4 channels of R vertically adjacent output pixels;
+// the input rows slide through registers so that every loaded row serves up to three outputs,
+// and the nine weight vectors are loaded once per thread.  Consecutive threads take consecutive
+// channel quads, then consecutive columns: all loads and stores are 16-byte and coalesced.
+// x [n][h][w][c], wt [9][c], y [n][oh][ow][c].
+template <int STRIDE, int R>
 __global__ __launch_bounds__(256) void dw3x3_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                    const float* __restrict__ wt, const float* __restrict__ bias,
-                                                   int h, int w, int c, int oh, int ow, int stride, int act,
-                                                   long long total)
+                                                   int h, int w, int c, int oh, int ow, int act, long long total)
 {
     const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
     if (t >= total) return;
     const int c4n = c >> 2;
     const int c4 = (int)(t % c4n) * 4;
+    long long r = t / c4n;
+    const int ox = (int)(r % ow);
+    r /= ow;
+    const int strips = (oh + R - 1) / R;
+    const int oy0 = (int)(r % strips) * R;
+    const long long b = r / strips;
+
+    v4f wv[9];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) wv[k] = *(const v4f*)(wt + k * c + c4);
+    const v4f bv = *(const v4f*)(bias + c4);
+    v4f acc[R];
+#pragma unroll
+    for (int i = 0; i < R; ++i) acc[i] = bv;
+
+    constexpr int ROWS = (R - 1) * STRIDE + 3;              // input rows touched by the strip
+    const int iy0 = oy0 * STRIDE - 1, ix0 = ox * STRIDE - 1;
+    const float* xb = x + b * h * w * c + c4;
+#pragma unroll
+    for (int ir = 0; ir < ROWS; ++ir) {
+        const int iy = iy0 + ir;
+        v4f row[3];
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx) {
+            const int ix = ix0 + kx;
+            const bool ok = iy >= 0 && iy < h && ix >= 0 && ix < w;
+            const v4f v = *(const v4f*)(xb + ((long long)(ok ? iy : 0) * w + (ok ? ix : 0)) * c);
+            row[kx] = ok ? v : (v4f){0.f, 0.f, 0.f, 0.f};
+        }
+        // input row ir is tap row ky of output i when ir == i*STRIDE + ky
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int ky = ir - i * STRIDE;
+            if (ky >= 0 && ky < 3) {
+#pragma unroll
+                for (int kx = 0; kx < 3; ++kx) acc[i] += row[kx] * wv[ky * 3 + kx];
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+        const int oy = oy0 + i;
+        if (oy >= oh) break;
+        v4f o = acc[i];
+        if (act == SBN_ACT_RELU) {
+            o.x = fmaxf(o.x, 0.f);
+            o.y = fmaxf(o.y, 0.f);
+            o.z = fmaxf(o.z, 0.f);
+            o.w = fmaxf(o.w, 0.f);
+        }
+        *(v4f*)(y + ((b * oh + oy) * (long long)ow + ox) * c + c4) = o;
+    }
+}
+
+// Dense 3x3 convolution of a few input channels (network stem), pad 1.  One thread: 4 output
+// channels of one output pixel; the (c_out x 9 x c_in) weights sit in LDS as [tap][ci][c_out].
+// x [n][h][w][c_in], y [n][oh][ow][c_out].
+__global__ __launch_bounds__(256) void stem3x3_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                     const float* __restrict__ wt, const float* __restrict__ bias,
+                                                     int h, int w, int c_in, int c_out, int oh, int ow, int stride,
+                                                     int act, long long total)
+{
+    __shared__ __attribute__((aligned(16))) float ws[9 * 4 * 64];
+    for (int i = threadIdx.x; i < 9 * c_in * c_out; i += 256) ws[i] = wt[i];
+    __syncthreads();
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const int c4n = c_out >> 2;
+    const int co = (int)(t % c4n) * 4;
     long long pix = t / c4n;
     const int ox = (int)(pix % ow);
     pix /= ow;
     const int oy = (int)(pix % oh);
     const long long b = pix / oh;
-    v4f acc = *(const v4f*)(bias + c4);
+    v4f acc = *(const v4f*)(bias + co);
 #pragma unroll
     for (int ky = 0; ky < 3; ++ky) {
         const int iy = oy * stride + ky - 1;
@@ -39,9 +112,9 @@ __global__ __launch_bounds__(256) void dw3x3_kernel(const float* __restrict__ x,
         for (int kx = 0; kx < 3; ++kx) {
             const int ix = ox * stride + kx - 1;
             if (ix < 0 || ix >= w) continue;
-            const v4f xv = *(const v4f*)(x + ((b * h + iy) * w + ix) * c + c4);
-            const v4f wv = *(const v4f*)(wt + (ky * 3 + kx) * c + c4);
-            acc += xv * wv;
+            const float* xp = x + ((b * h + iy) * w + ix) * c_in;
+            for (int ci = 0; ci < c_in; ++ci)
+                acc += xp[ci] * *(const v4f*)(ws + ((ky * 3 + kx) * c_in + ci) * c_out + co);
         }
     }
     if (act == SBN_ACT_RELU) {
@@ -50,7 +123,62 @@ __global__ __launch_bounds__(256) void dw3x3_kernel(const float* __restrict__ x,
         acc.z = fmaxf(acc.z, 0.f);
         acc.w = fmaxf(acc.w, 0.f);
     }
-    *(v4f*)(y + ((b * oh + oy) * (long long)ow + ox) * c + c4) = acc;
+    *(v4f*)(y + ((b * oh + oy) * (long long)ow + ox) * c_out + co) = acc;
+}
+
+// The usual stem (3 -> 32 channels): one thread computes all 32 output channels of one output
+// pixel.  Weight indices are compile-time constants, so the weights arrive through scalar loads
+// and are operands of the multiply-adds; the 27 inputs of the window sit in registers.
+template <int CIN, int COUT>
+__global__ __launch_bounds__(256) void stem3x3_fixed_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                           const float* __restrict__ wt,
+                                                           const float* __restrict__ bias, int h, int w, int oh,
+                                                           int ow, int stride, int act, long long total)
+{
+    constexpr int LS = COUT + 4;                           // LDS row stride (floats)
+    __shared__ __attribute__((aligned(16))) float tile[256 * LS];
+    const long long t0 = (long long)blockIdx.x * 256;
+    const long long t = t0 + threadIdx.x;
+    if (t < total) {
+        const int ox = (int)(t % ow);
+        const int oy = (int)((t / ow) % oh);
+        const long long b = t / ((long long)ow * oh);
+        float xin[9][CIN];
+#pragma unroll
+        for (int k = 0; k < 9; ++k) {
+            const int iy = oy * stride + k / 3 - 1, ix = ox * stride + k % 3 - 1;
+            const bool ok = iy >= 0 && iy < h && ix >= 0 && ix < w;
+            const float* xp = x + ((b * h + (ok ? iy : 0)) * w + (ok ? ix : 0)) * CIN;
+#pragma unroll
+            for (int ci = 0; ci < CIN; ++ci) {
+                const float v = xp[ci];
+                xin[k][ci] = ok ? v : 0.f;
+            }
+        }
+#pragma unroll
+        for (int c0 = 0; c0 < COUT; c0 += 4) {
+            v4f acc = *(const v4f*)(bias + c0);
+#pragma unroll
+            for (int k = 0; k < 9; ++k)
+#pragma unroll
+                for (int ci = 0; ci < CIN; ++ci) acc += xin[k][ci] * *(const v4f*)(wt + (k * CIN + ci) * COUT + c0);
+            if (act == SBN_ACT_RELU) {
+                acc.x = fmaxf(acc.x, 0.f);
+                acc.y = fmaxf(acc.y, 0.f);
+                acc.z = fmaxf(acc.z, 0.f);
+                acc.w = fmaxf(acc.w, 0.f);
+            }
+            *(v4f*)(tile + threadIdx.x * LS + c0) = acc;
+        }
+    }
+    // the workgroup's 256 pixels are contiguous in y: store them as full rows
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < COUT / 4; ++i) {
+        const int slot = i * 256 + threadIdx.x;
+        const int pl = slot / (COUT / 4), c0 = (slot % (COUT / 4)) * 4;
+        if (t0 + pl < total) *(v4f*)(y + (t0 + pl) * COUT + c0) = *(const v4f*)(tile + pl * LS + c0);
+    }
 }
 
 // x [n][hw][c] -> y [n][c]; one thread per (image, channel).
@@ -91,14 +219,40 @@ int launch_copy(const void* src, void* dst, size_t bytes, void* stream)
 int launch_dw3x3(const float* x, float* y, const float* w_dev, const float* b_dev, int n, int h, int w, int c,
                  int stride, int act, void* stream)
 {
+    constexpr int R = 4;
     const int oh = (h - 1) / stride + 1, ow = (w - 1) / stride + 1;
-    const long long total = (long long)n * oh * ow * (c / 4);
+    const long long total = (long long)n * ((oh + R - 1) / R) * ow * (c / 4);
     if (total == 0) return SBN_OK;
     const long long blocks = (total + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return fail(SBN_EINVAL, "depthwise layer too large for one launch");
-    hipLaunchKernelGGL(dw3x3_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, x, y, w_dev, b_dev, h,
-                       w, c, oh, ow, stride, act, total);
+    if (stride == 1)
+        hipLaunchKernelGGL((dw3x3_kernel<1, R>), dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, x, y, w_dev,
+                           b_dev, h, w, c, oh, ow, act, total);
+    else
+        hipLaunchKernelGGL((dw3x3_kernel<2, R>), dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, x, y, w_dev,
+                           b_dev, h, w, c, oh, ow, act, total);
     return check_launch("dw3x3");
+}
+
+int launch_stem3x3(const float* x, float* y, const float* w_dev, const float* b_dev, int n, int h, int w, int c_in,
+                   int c_out, int stride, int act, void* stream)
+{
+    const int oh = (h - 1) / stride + 1, ow = (w - 1) / stride + 1;
+    if (c_in == 3 && c_out == 32) {
+        const long long pixels = (long long)n * oh * ow;
+        if (pixels == 0) return SBN_OK;
+        if ((pixels + 255) / 256 > 0x7FFFFFFFll) return fail(SBN_EINVAL, "stem layer too large for one launch");
+        hipLaunchKernelGGL((stem3x3_fixed_kernel<3, 32>), dim3((unsigned)((pixels + 255) / 256)), dim3(256), 0,
+                           (hipStream_t)stream, x, y, w_dev, b_dev, h, w, oh, ow, stride, act, pixels);
+        return check_launch("stem3x3");
+    }
+    const long long total = (long long)n * oh * ow * (c_out / 4);
+    if (total == 0) return SBN_OK;
+    const long long blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFFll) return fail(SBN_EINVAL, "stem layer too large for one launch");
+    hipLaunchKernelGGL(stem3x3_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, x, y, w_dev, b_dev, h,
+                       w, c_in, c_out, oh, ow, stride, act, total);
+    return check_launch("stem3x3");
 }
 
 int launch_avgpool(const float* x, float* y, int n, int hw, int c, void* stream)

@@ -152,3 +152,72 @@ def test_chain_with_3x3_layer():
     h1, _ = R.sparse_conv_reference(x, w3, m3, 4, 4, stride=2, pad=1, act=R.ACT_RELU)
     ref, bound = R.conv_nhwc(h1, w1)
     np.testing.assert_allclose(yd.cpu().numpy(), ref, rtol=1e-4, atol=1e-5)
+
+
+def test_whole_mobilenet_chain_small_input():
+    """Config 4 at a small input (2 x 64 x 64 x 3): stem -> 13 x (dw, sparse pw) -> pool -> classifier,
+    every item checked against the oracle fed with the GPU's previous output."""
+    import bench
+    chain, meta = bench.build_mobilenet_chain(S, W, 50, max_iters=100)
+    n, hw = 2, 64
+    x = W.uniform_activation(9500, (n, hw, hw, 3))
+    oh, ow, oc = S.sbn_chain_output_shape(chain, n, hw, hw)
+    assert (oh, ow, oc) == (1, 1, 1000)
+    shapes, h, c = [], hw, 3
+    for m in meta:
+        if m["kind"] in ("dw", "stem"):
+            h = (h - 1) // m["stride"] + 1
+        if m["kind"] in ("pw", "stem"):
+            c = m["w"].shape[0]
+        if m["kind"] == "pool":
+            h = 1
+        shapes.append((n, h, h, c))
+    taps = [torch.full(s, float("nan"), device="cuda") for s in shapes]
+    ws = torch.empty(S.sbn_chain_workspace(chain, n, hw, hw) // 4, device="cuda")
+    yd = torch.empty(n, 1, 1, 1000, device="cuda")
+    S.sbn_pointwise_chain(chain, torch.from_numpy(x).cuda(), yd, n, hw, hw, ws, layer_outputs=taps)
+    torch.cuda.synchronize()
+    prev = x
+    for i, m in enumerate(meta):
+        out = taps[i].cpu().numpy()
+        if m["kind"] == "stem":
+            ref, bound = R.conv_nhwc(prev, m["w"], m["b"], stride=m["stride"], pad=1, act=R.ACT_RELU)
+        elif m["kind"] == "dw":
+            w, b = m["w"], m["b"]
+            if m["order"] is not None:
+                w, b = w[m["order"]], b[m["order"]]
+            ref, bound = R.dwconv3x3_nhwc(prev, w, b, stride=m["stride"], act=R.ACT_RELU)
+        elif m["kind"] == "pool":
+            ref, bound = R.avgpool_nhwc(prev)[:, None, None, :], None
+        else:
+            ref, bound = R.sparse_conv_reference(prev, m["w"], m["mask"], m["go"], 4, bias=m["b"], perm_out=m["po"],
+                                                 perm_in=m["pi"], act=m["act"])
+        if bound is None:
+            np.testing.assert_allclose(out, ref, rtol=0, atol=1e-5)
+        else:
+            assert_within_bound(out, ref, bound, f"mobilenet item {i} ({m['kind']})")
+        prev = out
+    assert np.array_equal(taps[-1].cpu().numpy(), yd.cpu().numpy())
+
+
+@pytest.mark.parametrize("c_in,c_out,stride,hw", [(2, 8, 1, 9), (4, 16, 2, 10), (3, 32, 2, 13), (1, 4, 1, 5)])
+def test_stem_item_alone(c_in, c_out, stride, hw):
+    w = W.he_weights(9600 + c_in, c_out, 3, 3, c_in)
+    b = W.small_bias(9601, c_out) * 10
+    chain = S.sbn_chain_create([S.stem_item(w, b, stride=stride, act=S.SBN_ACT_RELU)])
+    n = 3
+    x = W.uniform_activation(9602, (n, hw, hw, c_in))
+    oh, ow, oc = S.sbn_chain_output_shape(chain, n, hw, hw)
+    yd = torch.full((n, oh, ow, oc), float("nan"), device="cuda")
+    S.sbn_pointwise_chain(chain, torch.from_numpy(x).cuda(), yd, n, hw, hw, None)
+    torch.cuda.synchronize()
+    ref, bound = R.conv_nhwc(x, w, b, stride=stride, pad=1, act=R.ACT_RELU)
+    assert_within_bound(yd.cpu().numpy(), ref, bound, "stem")
+
+
+def test_stem_must_come_first():
+    w1 = W.he_weights(9700, 4, 1, 1, 4)
+    a = S.sbn_pack(S.SBN_CONV1X1, w1, 4, 4)
+    with pytest.raises(S.SbnError) as ei:
+        S.sbn_chain_create([S.sparse_item(a), S.stem_item(W.he_weights(9701, 8, 3, 3, 4))])
+    assert ei.value.code == -2

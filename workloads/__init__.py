@@ -171,3 +171,12 @@ def dw_layer_tensors(base_seed: int, layer: DwShape):
     w = normal_weights(s, (layer.c, 3, 3), float(np.sqrt(2.0 / 9.0)))
     b = small_bias(s + 100, layer.c)
     return dict(w=w, bias=b)
+
+
+def mobilenet_v1_tensors(base_seed: int = 4000):
+    """Random-init parameters of the whole network (config 4 recipe): stem, 13 x (dw, pw), classifier."""
+    stem = dict(w=he_weights(base_seed, STEM["c_out"], 3, 3, STEM["c_in"]), bias=small_bias(base_seed + 1, STEM["c_out"]))
+    dws = [dw_layer_tensors(base_seed, d) for d in MOBILENET_V1_DW]
+    pws = [pw_layer_tensors(base_seed, p, 1, with_x=False) for p in MOBILENET_V1_PW]
+    fc = dict(w=he_weights(base_seed + 900, FC["c_out"], 1, 1, FC["c_in"]), bias=small_bias(base_seed + 901, FC["c_out"]))
+    return dict(stem=stem, dw=dws, pw=pws, fc=fc)
