@@ -336,8 +336,8 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
         if (K <= 64) return launch<1, 2, 64, false, false>(p, x, y, M, st);
         return launch<1, 2, 64, true, false>(p, x, y, M, st);
     }
-    // one chunk, bound by HBM: 128 pixels per workgroup when there are plenty
-    const bool p2 = force ? force / 10 == 2 : M >= 128 * 1024;
+    // one chunk (HBM-bound layers): 64-pixel tiles keep more workgroups, hence more loads, in flight
+    const bool p2 = force / 10 == 2;
     if (K <= 32) return p2 ? launch<2, 1, 32, false, true>(p, x, y, M, st) : launch<1, 2, 32, false, true>(p, x, y, M, st);
     if (K <= 64) return p2 ? launch<2, 1, 64, false, true>(p, x, y, M, st) : launch<1, 2, 64, false, true>(p, x, y, M, st);
     int variant = force;
