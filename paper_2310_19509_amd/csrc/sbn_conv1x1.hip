@@ -1,10 +1,11 @@
 // Group-sparse 1x1 convolution for gfx950 (Algorithm 1 re-tiled for CDNA4).
 //
 // Mapping.  One lane owns one pixel (a wave owns 64*P pixels); a wave owns one
-// bundle of four 4-filter output groups, a workgroup of four waves owns four
-// bundles (64 output channels) over the same pixels.  The activation tile
-// X[64*P pixels][64 channels] is staged once per workgroup and chunk in LDS,
-// row stride 68 floats so that per-lane 16-byte row accesses are conflict free.
+// bundle of four 4-filter output groups (16 output channels); a workgroup of
+// four waves owns four bundles over the same pixels.  The activation tile
+// X[64*P pixels][KC channels] of a chunk is staged once per workgroup in LDS,
+// row stride KC+4 floats so that the per-lane 16-byte row reads are free of
+// bank conflicts.
 //
 // Inner step (one ENTRY = one 4-channel piece kept by at least one group of
 // the bundle): each lane reads its pixel's 4 channels from LDS (ds_read_b128
@@ -12,35 +13,19 @@
 // 4*P v_mfma_f32_4x4x1 (16 blocks each): block b multiplies the weight column
 // w[co 0..3][ci] -- broadcast from lanes 4*abid..4*abid+3 of a weight register
 // to all 16 blocks -- with the activations of pixels 4b..4b+3, so accumulator
-// register i of lane L holds output channel i of pixel L.  The staged
+// register i of lane L holds output channel i of pixel L.  That MFMA shape is
+// exactly one row of a 4x4 block: no padding, no idle lanes.  The staged
 // activation is reused by every group of the bundle that keeps the piece, a
-// weight register by every pixel set.  The weights of a whole 64-channel chunk
-// (at most 16 entries = 4 x 16-byte loads per lane) are fetched one chunk
-// ahead, together with the next activation chunk, while the current chunk is
-// being multiplied.  Dependent MFMAs stall the matrix pipe, so every (pixel
-// set, group) pair accumulates into 4/P interleaved partial sums.
+// weight register by every pixel set.  Group bits are tested with scalar
+// instructions on the wave-uniform descriptor.  The weights of a whole chunk
+// (16-byte loads per lane, four entries each) and the chunk's record of
+// descriptors (one scalar load) are fetched one chunk ahead.
 //
-// Epilogue: partial sums are added, bias and activation applied, the 64*P x 64
-// output tile is transposed through LDS and written with full-row 16-byte
-// stores (a wave instruction covers whole 256-byte rows).
+// Epilogue: partial sums are added, bias and activation applied, the output
+// tile is transposed through LDS and written as full rows of 16-byte stores.
 #include <hip/hip_runtime.h>
 
 #include "sbn_internal.h"
-
-#ifdef SBN_TRACE
-__device__ unsigned long long sbn_trace_buf[8 * 4 * 128];
-extern "C" int sbn_trace_read(unsigned long long* out)
-{
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(sbn_trace_buf), sizeof(unsigned long long) * 8 * 4 * 128);
-}
-#define SBN_TS(i)                                                                                         \
-    if (lane == 0 && (blockIdx.x % 200) == 0 && blockIdx.x / 200 < 8) {                                    \
-        sbn_trace_buf[((blockIdx.x / 200) * 4 + wave) * 128 + (i)] = __builtin_readcyclecounter();         \
-        if ((i) == 0 || (i) == 101) sbn_trace_buf[((blockIdx.x / 200) * 4 + wave) * 128 + (i) + 10] = wall_clock64(); \
-    }
-#else
-#define SBN_TS(i)
-#endif
 
 namespace {
 
@@ -53,16 +38,15 @@ __device__ __forceinline__ v4f mfma_bcast(float w, float x, v4f c)
     return __builtin_amdgcn_mfma_f32_4x4x1f32(w, x, c, 4, ABID, 0);
 }
 
-// acc[p][g][a]: pixel set p, group g, partial sum a.  An MFMA that adds to the
-// result of one issued fewer than three MFMAs earlier stalls the matrix pipe for
-// every wave, so the four input channels of a piece rotate over NA partial sums;
-// with NA = 3 the rotation also advances with the entry slot Q so that the
-// distance stays three across entries.
+// acc[p][g][a]: pixel set p, group g, partial sum a.  An MFMA that adds to the result of
+// the MFMA issued just before it has to wait for that result, so the four input channels
+// of a piece alternate over NA partial sums (with NA = 3 the rotation also advances with the
+// entry slot Q so that the distance stays three across entries).
 template <int P, int NA, int Q, int G>
 __device__ __forceinline__ void group_fma(const v4f& w, const v4f (&xv)[P], v4f (&acc)[P][4][NA])
 {
     constexpr int R = NA == 3 ? Q % 3 : 0;
-    constexpr int AB = (Q & 3) * 4 + G;
+    constexpr int AB = (Q & 3) * 4 + G;           // lanes 4*AB..4*AB+3 of w hold [co 0..3] of entry Q, group G
 #pragma unroll
     for (int p = 0; p < P; ++p) acc[p][G][(0 + R) % NA] = mfma_bcast<AB>(w.x, xv[p].x, acc[p][G][(0 + R) % NA]);
 #pragma unroll
@@ -202,7 +186,6 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
             load_weights(cn, w_nxt);
             r_nxt = recs[cn];
         }
-        SBN_TS(2 + c * 4)
 
         if (active) {
             const char* lds_lane = (const char*)xbuf + lane * (XS * 4);
@@ -240,22 +223,17 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
 #undef SBN_ENTRY
         chunk_done:;
         }
-        SBN_TS(3 + c * 4)
         if (MULTI) write_x(xnext);
-        SBN_TS(4 + c * 4)
         __syncthreads();                     // tile of the next chunk published / this one released
-        SBN_TS(5 + c * 4)
     };
 
     v4f w_a[NW], w_b[NW];
     Record<NS> r_a, r_b;
-    SBN_TS(0)
     issue_x(0);
     load_weights(0, w_a);
     r_a = recs[0];
     write_x(lds);
     __syncthreads();
-    SBN_TS(1)
     if (MULTI) {
         for (int c = 0; c < n_chunks; c += 2) {
             chunk(c, lds, lds_b, w_a, w_b, r_a, r_b);
@@ -302,7 +280,6 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
                 *(v4f*)(y + pix * N + ch_base + col) = *(const v4f*)(lds + row * XS + col);
         }
     }
-    SBN_TS(101)
 }
 
 template <int P, int NA, int KC, bool MULTI, bool VEC>

@@ -141,3 +141,58 @@ def test_full_size_batch64_sampled(layer_idx, pct, go):
     ys = yd[torch.from_numpy(idx).cuda()].cpu().numpy()
     ref, bound = R.sparse_conv_reference(xs[None, None], t["w"], mask, go, 4, bias=t["bias"], act=S.SBN_ACT_RELU)
     assert_within_bound(ys[None, None], ref, bound, f"pw{layer_idx} rho={pct} go={go}")
+
+
+def test_config2_all_13_layers_batch1_rearranged_chained_perms():
+    """Config 2: the 13 pointwise layers at batch 1, each on its own input, 30 % by block magnitude
+    after rearrangement, permutations chained across the stack; every output is compared."""
+    layers = [W.pw_layer_tensors(2000, L, 1) for L in W.MOBILENET_V1_PW]
+    descs = [dict(kind=S.SBN_CONV1X1, w=t["w"], go=4, gi=4) for t in layers]
+    perms = S.sbn_rearrange(descs, [-1] + list(range(12)), 30, seed=2000, max_iters=300,
+                            keep_output_order=[0] * 12 + [1])
+    pin = None
+    for L, t, po in zip(W.MOBILENET_V1_PW, layers, perms):
+        wp = R.permute_weights(t["w"], po, pin)
+        mask = S.sbn_prune_magnitude(wp, S.SBN_CONV1X1, 4, 4, 30)
+        assert np.array_equal(mask, R.prune_mask(wp, 4, 4, 30))
+        assert R.retained_l1(wp, 4, 4, 30) >= R.retained_l1(R.permute_weights(t["w"], None, pin), 4, 4, 30) * (1 - 1e-12)
+        x = t["x"] if pin is None else np.ascontiguousarray(t["x"][..., pin])
+        y, ref, bound = run_layer(x, t["w"], 4, 4, mask=mask, bias=t["bias"], perm_out=po, perm_in=pin,
+                                  act=S.SBN_ACT_RELU)
+        assert_within_bound(y, ref, bound, f"config2 pw{L.index}")
+        pin = po
+
+
+def test_config1_with_per_input_channel_masks():
+    """Secondary reading of 'group of 4 output channels sharing the input-channel mask': gi = 1."""
+    c = W.config1()
+    mask = W.uniform_block_mask(1004, 128 // 4, 64, (128 // 4) * 64 // 2)
+    y, ref, bound = run_layer(c["x"], c["w"], 4, 1, mask=mask)
+    assert_within_bound(y, ref, bound, "config1 gi=1")
+
+
+def test_very_wide_input():
+    """Many chunks, few outputs: c_in = 2048, c_out = 16, odd pixel count."""
+    w = W.he_weights(7301, 16, 1, 1, 2048)
+    x = W.uniform_activation(7302, (1, 1, 71, 2048))
+    y, ref, bound = run_layer(x, w, 4, 4, bias=W.small_bias(7303, 16), pct=60)
+    assert_within_bound(y, ref, bound, "wide K")
+
+
+def test_same_layer_on_two_streams_and_repeated_launches():
+    """Launches of one packed layer on different streams and buffers do not interfere."""
+    L = W.MOBILENET_V1_PW[4]
+    t = W.pw_layer_tensors(7400, L, 2)
+    mask = S.sbn_prune_magnitude(t["w"], S.SBN_CONV1X1, 4, 4, 50)
+    p = S.sbn_pack(S.SBN_CONV1X1, t["w"], 4, 4, mask=mask, bias=t["bias"])
+    xs = [torch.from_numpy(t["x"]).cuda(), torch.from_numpy(t["x"][::-1].copy()).cuda()]
+    ys = [torch.empty(2, L.hw, L.hw, L.c_out, device="cuda") for _ in range(2)]
+    sts = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for i in range(2):
+            S.sbn_conv1x1_sparse(p, xs[i], ys[i], 2, L.hw, L.hw, stream=sts[i])
+    torch.cuda.synchronize()
+    ref, bound = R.sparse_conv_reference(t["x"], t["w"], mask, 4, 4, bias=t["bias"])
+    assert_within_bound(ys[0].cpu().numpy(), ref, bound, "stream 0")
+    assert_within_bound(ys[1].cpu().numpy(), ref[::-1], bound[::-1], "stream 1")
