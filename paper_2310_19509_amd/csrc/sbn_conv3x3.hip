@@ -2,21 +2,34 @@
 // connectivity pruning: whole 3x3 kernels are kept or removed in groups).
 //
 // Same engine as the 1x1 kernel, with every kept piece carrying nine taps.
-// One lane owns one output pixel of an 8x8 spatial tile; a wave owns one
-// bundle of four 4-filter groups; the four waves of a workgroup share the
-// input tile ((8-1)*stride+3)^2 pixels x 32 channels, staged in LDS (pixel
-// stride 36 floats) through registers.  Input positions outside the image are
+// One lane owns PX horizontally adjacent output pixels of an (8*PX)x8 spatial
+// tile; a wave owns one bundle of four 4-filter groups (16 output channels);
+// the four waves of a workgroup share the input tile, 32 channels at a time,
+// staged in LDS through registers.  Input positions outside the image are
 // staged as zeros, which realises the zero padding.  For stride 1 the tile is
-// double buffered: the next 32 channels are fetched while the current ones are
-// multiplied and published with one barrier per sub-chunk.
+// double buffered: the next 32 channels are fetched while the current ones
+// are multiplied and are published with one barrier per sub-chunk.
+//
+// Every multiply consumes one activation scalar per lane, so the LDS read
+// rate is what saturates first: with PX = 2 the two pixels share two of their
+// three window columns, and all present groups of an entry share the window.
+// The LDS image is swizzled so that these 16-byte reads are free of bank
+// conflicts (see the kernel).
 //
 // Per entry (a 4-channel piece kept by at least one group of the bundle) the
-// lane reads the nine shifted 16-byte activation vectors of its window, the
-// wave loads the entry's 9 x 64 weights ([tap][group][ci][co], one float per
-// lane and tap), and for every present group issues 36 v_mfma_f32_4x4x1 with
-// the weight column broadcast from lanes 4*abid..4*abid+3.  Descriptors of a
-// 64-channel record are held one per lane and broadcast with v_readlane.
+// wave holds the entry's 9 x 64 weights ([tap][group][ci][co], one register
+// per tap, fetched one entry ahead) and walks the three rows of taps: the
+// lane reads the row's shifted 16-byte activation vectors (one row ahead of
+// the arithmetic) and, for every present group, issues 12 v_mfma_f32_4x4x1
+// per pixel: the weight column [co 0..3] of (group, ci) is broadcast from
+// lanes 4*abid..4*abid+3 to all 16 blocks and meets the activations of pixels
+// 4b..4b+3, so accumulator register i of lane L is output channel i of pixel
+// L.  Descriptors of a 64-channel record are held one per lane and broadcast
+// with v_readlane.
 #include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <type_traits>
 
 #include "sbn_internal.h"
 
@@ -24,10 +37,8 @@ namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int TW = 8, TH = 8;          // output tile
+constexpr int TH = 8;                  // output tile height (width: 8 * PX)
 constexpr int KC = 32;                 // channels staged at a time
-constexpr int RS = 9;                  // 16-byte slots per staged pixel (8 + padding)
-constexpr int XS = RS * 4;             // staged pixel stride in floats
 constexpr int OS = 68;                 // output tile row stride in floats
 
 template <int ABID>
@@ -36,39 +47,62 @@ __device__ __forceinline__ v4f mfma_bcast(float w, float x, v4f c)
     return __builtin_amdgcn_mfma_f32_4x4x1f32(w, x, c, 4, ABID, 0);
 }
 
-struct Entry {
-    float w[9];      // weights of the nine taps, lane l = [g][ci][co]
-    v4f x[9];        // this lane's activations under the nine taps
-};
-
-template <int G>
-__device__ __forceinline__ void group_fma(const Entry& s, v4f (&acc)[4][2])
+// One row of taps (ky = KY, kx = 0..2) of group G over the lane's PX pixels.  w[t] holds tap t,
+// lane l = [g][ci][co]; x holds the (PX-1)*STRIDE+3 input columns under the pixels.
+// PX = 1: acc[G][0/1] are two partial sums of the one pixel; PX = 2: acc[G][p] is pixel p.
+template <int G, int KY, int PX, int STRIDE, int NX>
+__device__ __forceinline__ void row_fma(const float (&w)[9], const v4f (&x)[NX], v4f (&acc)[4][2])
 {
 #pragma unroll
-    for (int t = 0; t < 9; ++t) {
-        acc[G][0] = mfma_bcast<G * 4 + 0>(s.w[t], s.x[t].x, acc[G][0]);
-        acc[G][1] = mfma_bcast<G * 4 + 1>(s.w[t], s.x[t].y, acc[G][1]);
-        acc[G][0] = mfma_bcast<G * 4 + 2>(s.w[t], s.x[t].z, acc[G][0]);
-        acc[G][1] = mfma_bcast<G * 4 + 3>(s.w[t], s.x[t].w, acc[G][1]);
+    for (int kx = 0; kx < 3; ++kx) {
+        const float wt = w[KY * 3 + kx];
+        if constexpr (PX == 1) {
+            acc[G][0] = mfma_bcast<G * 4 + 0>(wt, x[kx].x, acc[G][0]);
+            acc[G][1] = mfma_bcast<G * 4 + 1>(wt, x[kx].y, acc[G][1]);
+            acc[G][0] = mfma_bcast<G * 4 + 2>(wt, x[kx].z, acc[G][0]);
+            acc[G][1] = mfma_bcast<G * 4 + 3>(wt, x[kx].w, acc[G][1]);
+        } else {
+            const v4f x0 = x[kx], x1 = x[STRIDE + kx];
+            acc[G][0] = mfma_bcast<G * 4 + 0>(wt, x0.x, acc[G][0]);
+            acc[G][1] = mfma_bcast<G * 4 + 0>(wt, x1.x, acc[G][1]);
+            acc[G][0] = mfma_bcast<G * 4 + 1>(wt, x0.y, acc[G][0]);
+            acc[G][1] = mfma_bcast<G * 4 + 1>(wt, x1.y, acc[G][1]);
+            acc[G][0] = mfma_bcast<G * 4 + 2>(wt, x0.z, acc[G][0]);
+            acc[G][1] = mfma_bcast<G * 4 + 2>(wt, x1.z, acc[G][1]);
+            acc[G][0] = mfma_bcast<G * 4 + 3>(wt, x0.w, acc[G][0]);
+            acc[G][1] = mfma_bcast<G * 4 + 3>(wt, x1.w, acc[G][1]);
+        }
     }
 }
 
-template <int STRIDE>
+template <int STRIDE, int PX, bool DEEP>
 __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                       const uint32_t* __restrict__ records,
                                                       const uint32_t* __restrict__ woff,
                                                       const float* __restrict__ wts, const float* __restrict__ bias,
-                                                      const float* __restrict__ zeros, int H, int W, int OH, int OW,
+                                                      int H, int W, int OH, int OW,
                                                       int K, int N, int n_bundles, int n_chunks, int n_col_tiles,
                                                       int tiles_x, int tiles_y, int n_pix_tiles, int act)
 {
+    constexpr int TW = 8 * PX;                         // output tile width
+    constexpr int NX = (PX - 1) * STRIDE + 3;          // input columns under a lane's pixels
     constexpr int IW = (TW - 1) * STRIDE + 3;          // input tile width
     constexpr int IH = (TH - 1) * STRIDE + 3;
     constexpr int NPIX = IW * IH;                      // staged input pixels
     constexpr int NSLOT = NPIX * (KC / 4);             // 16-byte slots of a staged tile
     constexpr int NL = (NSLOT + 255) / 256;            // slots per thread
-    constexpr int XBUF = NPIX * XS;                    // floats per activation buffer
+    // LDS image of the tile: one 128-byte block per input pixel at block index
+    // row * IWP + col (+ 1 for stride 2 when row/2 is odd); inside the block the 16-byte slot of
+    // channels 4s..4s+3 sits at position s ^ g(col), g = col % 8 (PX = 1, stride 1) or
+    // (col / 2) % 8.  With an odd row pitch (stride 1) or the row shift (stride 2) the 16 lanes
+    // that a ds_read_b128 serves per cycle, two tile rows of 8 lanes, then hit 16 different
+    // 16-byte bank groups for every tap and piece.
+    constexpr int IWP = STRIDE == 2 ? IW + 1 : (IW | 1) == IW ? IW : IW + 1;
+    constexpr int XBUF = IH * IWP * 32;                // floats per activation buffer
     constexpr bool DB = STRIDE == 1;
+    struct XW {
+        v4f r[DEEP ? 3 : 1][NX];
+    };
     constexpr int OBUF = 64 * OS;
     __shared__ __attribute__((aligned(16))) float lds[XBUF > OBUF ? XBUF : OBUF];
     __shared__ __attribute__((aligned(16))) float lds_b[DB ? XBUF : 4];
@@ -94,96 +128,149 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
 #pragma unroll
     for (int g = 0; g < 4; ++g) acc[g][0] = acc[g][1] = (v4f){0.f, 0.f, 0.f, 0.f};
 
-    // ---- staging: thread t moves slots t, t+256, ...; slot = pixel * 8 + col
+    // ---- staging: thread t moves 16-byte slots t, t+256, ...; slot = pixel * 8 + column, so a
+    //      thread keeps its column and walks pixels t/8, t/8 + 32, ...  Positions outside the
+    //      image load some inside position and are replaced by zeros on the way to LDS.
     const float* xi = x + img * H * W * K;
-    const float* gpix[NL];        // channel 0 of the slot's input pixel (any valid address when outside)
-    int gcol[NL];
-    bool ginside[NL];
+    const int col4 = (threadIdx.x & 7) * 4;
+    int goff[NL];                 // element offset of the slot's (clamped) input pixel in the image
+    uint32_t inside = 0;          // bit i: slot i is a real position
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-        int s = i * 256 + threadIdx.x;
-        s = s < NSLOT ? s : NSLOT - 1;
-        const int pix = s / (KC / 4), col = s % (KC / 4);
+        int pix = i * 32 + (threadIdx.x >> 3);
+        pix = pix < NPIX ? pix : NPIX - 1;
         const int iy = iy0 + pix / IW, ix = ix0 + pix % IW;
-        ginside[i] = iy >= 0 && iy < H && ix >= 0 && ix < W;
-        gpix[i] = ginside[i] ? xi + ((long long)iy * W + ix) * K : zeros;
-        gcol[i] = col * 4;
+        if (iy >= 0 && iy < H && ix >= 0 && ix < W) inside |= 1u << i;
+        goff[i] = (min(max(iy, 0), H - 1) * W + min(max(ix, 0), W - 1)) * K;
     }
     v4f stage_reg[NL];
     auto issue_x = [&](int sc) {
+        const int ch = min(col4 + sc * KC, K - 4);      // keep the 16-byte read inside the pixel's channels
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            // keep the 16-byte read inside the pixel's channels; outside the image read zeros
-            const int ch = ginside[i] ? min(gcol[i] + sc * KC, K - 4) : 0;
-            stage_reg[i] = *(const v4f*)(gpix[i] + ch);
-        }
+        for (int i = 0; i < NL; ++i) stage_reg[i] = *(const v4f*)(xi + goff[i] + ch);
     };
     auto write_x = [&](float* buf) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int s = i * 256 + threadIdx.x;
-            if (s < NSLOT) *(v4f*)(buf + (s / (KC / 4)) * XS + (s % (KC / 4)) * 4) = stage_reg[i];
+            const int pix = i * 32 + (threadIdx.x >> 3);
+            const v4f v = (inside >> i) & 1u ? stage_reg[i] : (v4f){0.f, 0.f, 0.f, 0.f};
+            const int r = pix / IW, c = pix % IW;
+            const int g = PX == 1 && STRIDE == 1 ? c & 7 : (c >> 1) & 7;
+            const int blk = r * IWP + c + (STRIDE == 2 ? (r >> 1) & 1 : 0);
+            if (pix < NPIX) *(v4f*)(buf + blk * 32 + (((col4 >> 2) ^ g) << 2)) = v;
         }
     };
 
     // this lane's window origin inside the staged tile
-    const int oyl = lane / TW, oxl = lane % TW;
-    const int lane_off = ((oyl * STRIDE) * IW + oxl * STRIDE) * (XS * 4);      // bytes
+    const int oyl = lane / 8, oxl = (lane % 8) * PX;       // first of the lane's PX pixels
+    const int row0 = oyl * STRIDE, col0 = oxl * STRIDE;
+    constexpr int NG = PX == 1 && STRIDE == 1 ? 3 : 2;     // distinct g among the lane's columns
+    int xrow[3], g16[NG];           // byte offsets of the window's rows relative to row 0's pitch; g << 4
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky)      // stride 1: all three equal, the row pitch becomes an immediate
+        xrow[ky] = (row0 * IWP + col0 + (STRIDE == 2 ? ((row0 + ky) >> 1) & 1 : 0)) * 128;
+#pragma unroll
+    for (int j = 0; j < NG; ++j) g16[j] = ((PX == 1 && STRIDE == 1 ? col0 + j : (col0 >> 1) + j) & 7) << 4;
 
     const uint32_t* wo = woff + (size_t)bsafe * (n_chunks + 1);
     const uint32_t* recs = records + (size_t)bsafe * n_chunks * 16;
     const int n_sub = (K + KC - 1) / KC;
 
+    // weights of entry en: one register per tap, lane l = [g][ci][co]
+    auto load_w = [&](uint32_t en, float (&w)[9]) {
+        const float* wp = wts + (size_t)en * 576 + lane;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) w[t] = wp[t * 64];
+    };
+    float wa[9], wb[9];       // weights of the current and of the next entry of the bundle's list
     uint32_t dv = 0;          // descriptors of the current 64-channel record, one per lane (lanes 0..15)
-    uint32_t q = 0, e = 0;
+    uint32_t q = 0, e = 0;    // position in the record, running entry index
+
     // One sub-chunk of 32 channels: fetch the next one, multiply this one, publish the next.
     auto sub_chunk = [&](int sc, const float* xbuf, float* xnext) {
-        if (DB) issue_x(sc + 1 < n_sub ? sc + 1 : sc);      // unconditional: see the 1x1 kernel
+        if (DB) issue_x(sc + 1 < n_sub ? sc + 1 : sc);      // unconditional: loads under a branch
+                                                            // would be waited for before the arithmetic
         const uint32_t h = sc & 1;
-        if (h == 0) {
+        if (h == 0) {                                       // a new 64-channel record
             dv = recs[(sc >> 1) * 16 + (lane & 15)];
             q = 0;
-            e = __builtin_amdgcn_readfirstlane(wo[sc >> 1]);
         }
 
         if (active) {
-            const char* xl = (const char*)xbuf + lane_off;
+            const char* xl = (const char*)xbuf;
             auto desc = [&](uint32_t qq) -> uint32_t {
                 return qq < 16 ? (uint32_t)__builtin_amdgcn_readlane((int)dv, (int)qq) : 0u;
             };
             auto mine = [&](uint32_t d) { return d != 0 && ((d >> 11) & 1u) == h; };
-            auto load = [&](uint32_t en, uint32_t d, Entry& s) {
-                const float* wp = wts + (size_t)en * 576 + lane;
-                const char* xp = xl + ((d >> 8) & 7u) * 16;
+            // activations under one row of taps of the piece named by descriptor d
+            auto load_x = [&](uint32_t d, int ky, v4f (&xr)[NX]) {
+                const int s16 = (int)((d >> 8) & 7u) << 4;
 #pragma unroll
-                for (int t = 0; t < 9; ++t) {
-                    s.w[t] = wp[t * 64];
-                    s.x[t] = *(const v4f*)(xp + ((t / 3) * IW + (t % 3)) * (XS * 4));
+                for (int c = 0; c < NX; ++c) {
+                    const int j = PX == 1 && STRIDE == 1 ? c : c >> 1;
+                    xr[c] = *(const v4f*)(xl + (xrow[ky] + (s16 ^ g16[j])) + (ky * IWP + c) * 128);
                 }
             };
-            auto compute = [&](const Entry& s, uint32_t m) {
-                if (__builtin_expect((m & 1u) != 0, 1)) group_fma<0>(s, acc);
-                if (__builtin_expect((m & 2u) != 0, 1)) group_fma<1>(s, acc);
-                if (__builtin_expect((m & 4u) != 0, 1)) group_fma<2>(s, acc);
-                if (__builtin_expect((m & 8u) != 0, 1)) group_fma<3>(s, acc);
+            auto row = [&](auto kytag, uint32_t m, const float (&w)[9], const v4f (&xr)[NX]) {
+                constexpr int KY = decltype(kytag)::value;
+                // a taken branch costs the wave tens of cycles: keep "present" the fall-through path
+                if (__builtin_expect((m & 1u) != 0, 1)) row_fma<0, KY, PX, STRIDE, NX>(w, xr, acc);
+                if (__builtin_expect((m & 2u) != 0, 1)) row_fma<1, KY, PX, STRIDE, NX>(w, xr, acc);
+                if (__builtin_expect((m & 4u) != 0, 1)) row_fma<2, KY, PX, STRIDE, NX>(w, xr, acc);
+                if (__builtin_expect((m & 8u) != 0, 1)) row_fma<3, KY, PX, STRIDE, NX>(w, xr, acc);
             };
-            // Data run one entry ahead of the arithmetic.  A prefetch past the
-            // sub-chunk's last entry reads the weight array's slack or the next
-            // entry's weights and some in-tile activations; it is never used.
+            // One entry.  Its weights are in w; the next entry's are fetched into w_nxt meanwhile.
+            // Row-ahead (!DEEP): on entry p holds the activations under its first row of taps, on exit
+            // r holds those of the next entry's first row.  Entry-ahead (DEEP, for launches with so
+            // few waves per SIMD that latency counts): p holds the whole window and r receives the
+            // next entry's.  Either way consecutive entries swap the two register sets.  A fetch past
+            // the sub-chunk's last entry reads the next entry's weights (or the array's slack) and
+            // some in-tile activations; they are the next sub-chunk's or unused.
+            auto entry = [&](uint32_t d, uint32_t d_nxt, const float (&w)[9], float (&w_nxt)[9], XW& p, XW& r) {
+                load_w(e + 1, w_nxt);
+                if constexpr (DEEP) {
+                    load_x(d_nxt, 0, r.r[0]);
+                    load_x(d_nxt, 1, r.r[1]);
+                    load_x(d_nxt, 2, r.r[2]);
+                    auto group = [&](auto gtag) {
+                        constexpr int G = decltype(gtag)::value;
+                        row_fma<G, 0, PX, STRIDE, NX>(w, p.r[0], acc);
+                        row_fma<G, 1, PX, STRIDE, NX>(w, p.r[1], acc);
+                        row_fma<G, 2, PX, STRIDE, NX>(w, p.r[2], acc);
+                    };
+                    if (__builtin_expect((d & 1u) != 0, 1)) group(std::integral_constant<int, 0>{});
+                    if (__builtin_expect((d & 2u) != 0, 1)) group(std::integral_constant<int, 1>{});
+                    if (__builtin_expect((d & 4u) != 0, 1)) group(std::integral_constant<int, 2>{});
+                    if (__builtin_expect((d & 8u) != 0, 1)) group(std::integral_constant<int, 3>{});
+                } else {
+                    load_x(d, 1, r.r[0]);
+                    row(std::integral_constant<int, 0>{}, d, w, p.r[0]);
+                    load_x(d, 2, p.r[0]);
+                    row(std::integral_constant<int, 1>{}, d, w, r.r[0]);
+                    load_x(d_nxt, 0, r.r[0]);
+                    row(std::integral_constant<int, 2>{}, d, w, p.r[0]);
+                }
+            };
             uint32_t d_cur = desc(q);
             if (mine(d_cur)) {
-                Entry a, b;
-                load(e, d_cur, a);
+                XW xa, xb;
+                load_x(d_cur, 0, xa.r[0]);
+                if constexpr (DEEP) {
+                    load_x(d_cur, 1, xa.r[1]);
+                    load_x(d_cur, 2, xa.r[2]);
+                }
                 for (;;) {
                     uint32_t d_nxt = desc(q + 1);
-                    load(e + 1, d_nxt, b);
-                    compute(a, d_cur);
+                    entry(d_cur, d_nxt, wa, wb, xa, xb);
                     ++q, ++e;
                     d_cur = d_nxt;
-                    if (!mine(d_cur)) break;
+                    if (!mine(d_cur)) {              // the fetched weights belong to the next sub-chunk:
+#pragma unroll
+                        for (int t = 0; t < 9; ++t) wa[t] = wb[t];      // keep them where it expects them
+                        break;
+                    }
                     d_nxt = desc(q + 1);
-                    load(e + 1, d_nxt, a);
-                    compute(b, d_cur);
+                    entry(d_cur, d_nxt, wb, wa, xb, xa);
                     ++q, ++e;
                     d_cur = d_nxt;
                     if (!mine(d_cur)) break;
@@ -199,6 +286,8 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
     };
 
     issue_x(0);
+    e = __builtin_amdgcn_readfirstlane(wo[0]);
+    load_w(e, wa);
     write_x(lds);
     __syncthreads();
     for (int sc = 0; sc < n_sub; sc += 2) {
@@ -206,46 +295,53 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
         if (sc + 1 < n_sub) sub_chunk(sc + 1, DB ? lds_b : lds, lds);
     }
 
-    // ---- epilogue: bias, activation, transpose through LDS, full 256-byte rows per pixel
-    if (active) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            v4f o = acc[g][0] + acc[g][1] + *(const v4f*)(bias + bundle * 16 + g * 4);
-            if (act == SBN_ACT_RELU) {
-                o.x = fmaxf(o.x, 0.f);
-                o.y = fmaxf(o.y, 0.f);
-                o.z = fmaxf(o.z, 0.f);
-                o.w = fmaxf(o.w, 0.f);
-            }
-            *(v4f*)(lds + lane * OS + wave * 16 + g * 4) = o;
-        }
-    }
-    __syncthreads();
+    // ---- epilogue: bias, activation, transpose through LDS, full 256-byte rows per pixel;
+    //      one pass per pixel of the lane
     const int ch_base = col_tile * 64;
     float* yi = y + img * OH * OW * N;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int slot = i * 256 + threadIdx.x;
-        const int pl = slot >> 4, col = (slot & 15) * 4;
-        const int oy = oy0 + pl / TW, ox = ox0 + pl % TW;
-        if (oy < OH && ox < OW && ch_base + col < N)
-            *(v4f*)(yi + ((long long)oy * OW + ox) * N + ch_base + col) = *(const v4f*)(lds + pl * OS + col);
+    for (int p = 0; p < PX; ++p) {
+        if (p) __syncthreads();
+        if (active) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                v4f o = (PX == 1 ? acc[g][0] + acc[g][1] : acc[g][p]) + *(const v4f*)(bias + bundle * 16 + g * 4);
+                if (act == SBN_ACT_RELU) {
+                    o.x = fmaxf(o.x, 0.f);
+                    o.y = fmaxf(o.y, 0.f);
+                    o.z = fmaxf(o.z, 0.f);
+                    o.w = fmaxf(o.w, 0.f);
+                }
+                *(v4f*)(lds + lane * OS + wave * 16 + g * 4) = o;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int slot = i * 256 + threadIdx.x;
+            const int pl = slot >> 4, col = (slot & 15) * 4;             // pl: the lane that owned the pixel
+            const int oy = oy0 + pl / 8, ox = ox0 + (pl % 8) * PX + p;
+            if (oy < OH && ox < OW && ch_base + col < N)
+                *(v4f*)(yi + ((long long)oy * OW + ox) * N + ch_base + col) = *(const v4f*)(lds + pl * OS + col);
+        }
     }
 }
 
-template <int STRIDE>
+template <int STRIDE, int PX, bool DEEP>
 int launch(const sbn_packed* p, const float* x, float* y, int n, int h, int w, hipStream_t st)
 {
     const sbn::DeviceLayout& L = p->dev;
     const int oh = (h - 1) / STRIDE + 1, ow = (w - 1) / STRIDE + 1;
-    const int tiles_x = (ow + TW - 1) / TW, tiles_y = (oh + TH - 1) / TH;
+    const int tiles_x = (ow + 8 * PX - 1) / (8 * PX), tiles_y = (oh + TH - 1) / TH;
     const long long n_pix_tiles = (long long)n * tiles_x * tiles_y;
     const int n_col_tiles = (L.n_bundles + 3) / 4;
     const long long grid = ((n_pix_tiles + 7) / 8) * 8 * n_col_tiles;
+    if ((long long)h * w * p->c_in > 0x7FFFFFFFll)
+        return sbn::fail(SBN_EINVAL, "one image of %d x %d x %d elements is too large for 32-bit offsets", h, w, p->c_in);
     if (grid > 0x7FFFFFFFll || n_pix_tiles > 0x7FFFFFFFll)
         return sbn::fail(SBN_EINVAL, "too many output tiles for one launch (%lld)", n_pix_tiles);
-    hipLaunchKernelGGL((conv3x3_kernel<STRIDE>), dim3((unsigned)grid), dim3(256), 0, st, x, y, L.d_records, L.d_woff,
-                       L.d_wts, L.d_bias, L.d_zeros, h, w, oh, ow, p->c_in, p->c_out, L.n_bundles, L.n_chunks,
+    hipLaunchKernelGGL((conv3x3_kernel<STRIDE, PX, DEEP>), dim3((unsigned)grid), dim3(256), 0, st, x, y, L.d_records, L.d_woff,
+                       L.d_wts, L.d_bias, h, w, oh, ow, p->c_in, p->c_out, L.n_bundles, L.n_chunks,
                        n_col_tiles, tiles_x, tiles_y, (int)n_pix_tiles, p->act);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return sbn::fail(SBN_EHIP, "conv3x3 launch: %s", hipGetErrorString(e));
@@ -260,8 +356,26 @@ int launch_conv3x3(const sbn_packed* p, const float* x, float* y, int n, int h, 
 {
     if (p->c_in % 4)
         return fail(SBN_ESHAPE, "3x3 layers need c_in to be a multiple of 4 on the device (got %d)", p->c_in);
-    return p->stride == 1 ? launch<1>(p, x, y, n, h, w, (hipStream_t)stream)
-                          : launch<2>(p, x, y, n, h, w, (hipStream_t)stream);
+    hipStream_t st = (hipStream_t)stream;
+    if (p->stride == 2) return launch<2, 1, false>(p, x, y, n, h, w, st);
+    // Variant: two pixels per lane unless the 16-wide tiles would be mostly empty or would leave
+    // the chip short of waves; with at most about two waves per SIMD the entry-ahead variant.
+    static const int forced = [] {
+        const char* e = getenv("SBN_K3_VARIANT");
+        return e ? atoi(e) : 0;
+    }();
+    int variant = forced;
+    if (!variant) {
+        const long long col_tiles = (p->dev.n_bundles + 3) / 4;
+        const long long wg1 = (long long)n * ((w + 7) / 8) * ((h + 7) / 8) * col_tiles;
+        const long long wg2 = (long long)n * ((w + 15) / 16) * ((h + 7) / 8) * col_tiles;
+        variant = w > 8 && wg2 >= 2 * 256 ? 2 : wg1 <= 2 * 256 ? 3 : 1;
+    }
+    switch (variant) {
+    case 2: return launch<1, 2, false>(p, x, y, n, h, w, st);
+    case 3: return launch<1, 1, true>(p, x, y, n, h, w, st);
+    default: return launch<1, 1, false>(p, x, y, n, h, w, st);
+    }
 }
 
 }  // namespace sbn
