@@ -25,9 +25,10 @@ PEAK_HBM_GBS = 8000.0             # MI355X published HBM3E bandwidth
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--workload", default="pw13", choices=["pw13", "mobilenet", "conv3x3"],
+    ap.add_argument("--workload", default="pw13", choices=["pw13", "mobilenet", "conv3x3", "sweep"],
                     help="pw13: the 13 pointwise layers (headline metric); mobilenet: the whole network as one "
-                         "chain, batch 64, 50 %% sparsity; conv3x3: ResNet-50-shaped 3x3 layers, batch 32, 70 %%")
+                         "chain, batch 64, 50 %% sparsity; conv3x3: ResNet-50-shaped 3x3 layers, batch 32, 70 %%; "
+                         "sweep: the pointwise stack at 0/30/50/70/90 %% sparsity and go 4/8 against all groups kept")
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--batch", type=int, default=64)
@@ -241,6 +242,65 @@ def run_conv3x3(a, torch, S, W):
     print(json.dumps(out))
 
 
+def run_sweep(a, torch, S, W):
+    """Config 3: the 13-layer pointwise stack at batch 64 over sparsities and group sizes; the
+    comparison is the same kernel with every group kept (sparsity 0 of the same go)."""
+    B = a.batch
+    g = torch.Generator(device="cuda").manual_seed(3000)
+    xs = [torch.rand((B * L.hw * L.hw, L.c_in), device="cuda", generator=g) * 2 - 1 for L in W.MOBILENET_V1_PW]
+    ys = [torch.empty((B * L.hw * L.hw, L.c_out), device="cuda") for L in W.MOBILENET_V1_PW]
+    main_s = torch.cuda.current_stream()
+    side = [torch.cuda.Stream() for _ in range(max(2, a.streams))]
+
+    def run(packed, streams, steps, warmup):
+        def step():
+            for i, (L, p) in enumerate(zip(W.MOBILENET_V1_PW, packed)):
+                S.sbn_conv1x1_sparse(p, xs[i], ys[i], B, L.hw, L.hw, stream=streams[i % len(streams)])
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(main_s)
+        for st in streams:
+            st.wait_event(e0)
+        for _ in range(steps):
+            step()
+        for st in streams:
+            ev = torch.cuda.Event()
+            ev.record(st)
+            main_s.wait_event(ev)
+        e1.record(main_s)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    rows = []
+    for go in (4, 8):
+        base = None
+        for pct in (0, 30, 50, 70, 90):
+            _, _, packed, _ = build_layers(S, W, B, pct, go, pct > 0 and not a.no_rearrange)
+            fl = sum(2.0 * S.sbn_packed_work(p)["macs_per_pixel"] * B * L.hw * L.hw
+                     for L, p in zip(W.MOBILENET_V1_PW, packed))
+            ms_serial = run(packed, [main_s], a.steps, a.warmup)
+            ms_multi = run(packed, side, a.steps, a.warmup)
+            base = base or (ms_serial, ms_multi)
+            rows.append(dict(go=go, sparsity=pct, nonzero_gflop=round(fl / 1e9, 2),
+                             serial_ms=round(ms_serial, 4), serial_tflops=round(fl / ms_serial / 1e9, 2),
+                             serial_speedup_vs_kept=round(base[0] / ms_serial, 3),
+                             overlapped_ms=round(ms_multi, 4), overlapped_tflops=round(fl / ms_multi / 1e9, 2),
+                             overlapped_speedup_vs_kept=round(base[1] / ms_multi, 3)))
+            print(rows[-1], file=sys.stderr, flush=True)
+            torch.cuda.synchronize()
+            for p in packed:
+                S.sbn_free(p)
+    print(json.dumps({
+        "metric": "speedup of the group-sparse 1x1 stack over the same kernel with all groups kept",
+        "value": next(r["overlapped_speedup_vs_kept"] for r in rows if r["go"] == 4 and r["sparsity"] == 30),
+        "unit": "x at 30% sparsity, go=4", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"13 MobileNet-v1 pointwise layers, batch {B}, fp32, sparsity 0/30/50/70/90 %, go 4 and 8, gi 4"},
+        "rows": rows}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -256,6 +316,8 @@ def main():
         return run_mobilenet(a, torch, S, W)
     if a.workload == "conv3x3":
         return run_conv3x3(a, torch, S, W)
+    if a.workload == "sweep":
+        return run_sweep(a, torch, S, W)
     B = a.batch
     tens, perms, packed, pack_ms = build_layers(S, W, B, a.sparsity, a.go, not a.no_rearrange)
     dense = [] if a.no_dense else [S.sbn_pack(S.SBN_CONV1X1, t["w"], a.go, 4, bias=t["bias"], act=S.SBN_ACT_RELU,
