@@ -25,10 +25,11 @@ PEAK_HBM_GBS = 8000.0             # MI355X published HBM3E bandwidth
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--workload", default="pw13", choices=["pw13", "mobilenet", "conv3x3", "sweep"],
+    ap.add_argument("--workload", default="pw13", choices=["pw13", "mobilenet", "conv3x3", "sweep", "copy"],
                     help="pw13: the 13 pointwise layers (headline metric); mobilenet: the whole network as one "
                          "chain, batch 64, 50 %% sparsity; conv3x3: ResNet-50-shaped 3x3 layers, batch 32, 70 %%; "
-                         "sweep: the pointwise stack at 0/30/50/70/90 %% sparsity and go 4/8 against all groups kept")
+                         "sweep: the pointwise stack at 0/30/50/70/90 %% sparsity and go 4/8 against all groups kept; "
+                         "copy: the library's device copy kernel on 256 MiB (measured HBM roof, counter calibration)")
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--batch", type=int, default=64)
@@ -41,6 +42,33 @@ def parse():
                     help="HIP streams the 13 independent layers of a step are spread over (1 = strictly serial)")
     ap.add_argument("--no-dense", action="store_true", help="skip the all-groups-kept comparison run")
     return ap.parse_args()
+
+
+def profiled_traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 counter summary of this workload, or None."""
+    tf = os.path.join(ROOT, "profiles", name)
+    if os.path.exists(tf):
+        for line in open(tf):
+            if line.startswith("traffic_bytes_per_launch="):
+                return float(line.split("=")[1])
+    return None
+
+
+def run_copy(a, torch, S):
+    """Device-to-device copy of 256 MiB with the library's copy kernel: the HBM rate a plain
+    streaming kernel reaches on this machine, and the known-size dispatch that the FETCH_SIZE /
+    WRITE_SIZE counters are calibrated against."""
+    n = 256 << 20
+    src = torch.ones(n // 4, device="cuda")
+    dst = torch.empty(n // 4, device="cuda")
+    ms = time_steps(torch, lambda: S.sbn_copy_bytes(src, dst, n), a.steps, a.warmup)
+    gbs = 2.0 * n / (ms * 1e-3) / 1e9
+    print(json.dumps({"metric": "device copy bandwidth (read + write)", "value": round(gbs, 1), "unit": "GB/s",
+                      "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4),
+                      "higher_is_better": True, "dtype": "u8", "data": "synthetic",
+                      "config": {"workload": "sbn_copy_bytes, 256 MiB read + 256 MiB written per launch"},
+                      "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                   "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": 2.0 * n}}))
 
 
 def build_layers(S, W, batch, pct, go, rearrange):
@@ -189,12 +217,17 @@ def run_mobilenet(a, torch, S, W):
 def run_conv3x3(a, torch, S, W):
     """Config 5: ResNet-50-shaped 3x3 layers, batch 32, kernel-level group sparsity 70 %."""
     B, pct = 32 if a.batch == 64 else a.batch, 70 if a.sparsity == 30 else a.sparsity
-    layers, flops, xs, ys, hws = [], [], [], [], []
+    layers, dense, flops, bytes_alg, xs, ys, hws = [], [], [], [], [], [], []
     for idx in range(len(W.RESNET50_3X3)):
         t = W.conv3x3_layer_tensors(5000, idx, B, with_x=False)
         mask = S.sbn_prune_magnitude(t["w"], S.SBN_CONV3X3, a.go, 4, pct)
         p = S.sbn_pack(S.SBN_CONV3X3, t["w"], a.go, 4, mask=mask, bias=t["bias"], act=S.SBN_ACT_RELU, device=0)
         layers.append(p)
+        if not a.no_dense:
+            dense.append(S.sbn_pack(S.SBN_CONV3X3, t["w"], a.go, 4, bias=t["bias"], act=S.SBN_ACT_RELU, device=0))
+        work = S.sbn_packed_work(p)
+        bytes_alg.append(4.0 * B * t["hw"] ** 2 * 2 * t["c"] + work["nnz_blocks"] * (4 * 9 * a.go * 4 + 2)
+                         + 4 * (t["c"] // a.go + 1) + 4 * t["c"])
         hws.append(t["hw"])
         xs.append(torch.rand((B, t["hw"], t["hw"], t["c"]), device="cuda") * 2 - 1)
         ys.append(torch.empty((B, t["hw"], t["hw"], t["c"]), device="cuda"))
@@ -222,11 +255,17 @@ def run_conv3x3(a, torch, S, W):
     e1.record(main)
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / a.steps
+    # every layer alone on one stream: the kernel's own launch durations (what rocprofv3 reports)
     per = []
     for i, p in enumerate(layers):
-        t = time_steps(torch, lambda: S.sbn_conv3x3_sparse(p, xs[i], ys[i], B, hws[i], hws[i]), 50, 10) * 1e-3
-        per.append(dict(c=W.RESNET50_3X3[i][0], hw=hws[i], us=round(t * 1e6, 1), tflops=round(flops[i] / t / 1e12, 2)))
-    ach = sum(flops) / len(layers) / (ms * 1e-3 / len(layers)) / 1e12
+        t = time_steps(torch, lambda: S.sbn_conv3x3_sparse(p, xs[i], ys[i], B, hws[i], hws[i]), 100, 20) * 1e-3
+        r = dict(c=W.RESNET50_3X3[i][0], hw=hws[i], us=round(t * 1e6, 1), tflops=round(flops[i] / t / 1e12, 2))
+        if dense:
+            td = time_steps(torch, lambda: S.sbn_conv3x3_sparse(dense[i], xs[i], ys[i], B, hws[i], hws[i]), 50, 10) * 1e-3
+            r.update(all_kept_us=round(td * 1e6, 1), speedup_vs_all_kept=round(td / t, 3))
+        per.append(r)
+    avg_launch_s = sum(r["us"] for r in per) * 1e-6 / len(per)
+    ach = sum(flops) / len(layers) / avg_launch_s / 1e12
     out = {
         "metric": "effective GFLOP/s (nonzero FLOPs), ResNet-50-shaped 3x3 layers", "value": round(sum(flops) / (ms * 1e-3) / 1e9, 1),
         "unit": "GFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4),
@@ -235,9 +274,13 @@ def run_conv3x3(a, torch, S, W):
                                f"kernel-level group sparsity {pct}% (go={a.go} gi=4 whole kernels)", "batch": B,
                    "sparsity_percent": pct},
         "roofline": {"bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(ach / PEAK_MFMA_F32_TFLOPS, 4), "traffic": None,
-                     "kernel": "conv3x3_kernel<1> (4 launches per step)"},
-        "extra": {"streams": len(side), "per_layer": per},
+                     "frac": round(ach / PEAK_MFMA_F32_TFLOPS, 4),
+                     "traffic": profiled_traffic("conv3x3_r50_b32_rho70_traffic.txt") if (B, pct, a.go) == (32, 70, 4) else None,
+                     "kernel": "conv3x3_kernel (4 launches per step, one per layer; durations from serial single-stream passes)",
+                     "avg_launch_us": round(avg_launch_s * 1e6, 2)},
+        "extra": {"streams": len(side), "serial_ms_per_step": round(avg_launch_s * len(per) * 1e3, 4),
+                  "nonzero_gflop_per_step": round(sum(flops) / 1e9, 3),
+                  "algorithmic_bytes_per_launch": round(sum(bytes_alg) / len(per)), "per_layer": per},
     }
     print(json.dumps(out))
 
@@ -318,6 +361,8 @@ def main():
         return run_conv3x3(a, torch, S, W)
     if a.workload == "sweep":
         return run_sweep(a, torch, S, W)
+    if a.workload == "copy":
+        return run_copy(a, torch, S)
     B = a.batch
     tens, perms, packed, pack_ms = build_layers(S, W, B, a.sparsity, a.go, not a.no_rearrange)
     dense = [] if a.no_dense else [S.sbn_pack(S.SBN_CONV1X1, t["w"], a.go, 4, bias=t["bias"], act=S.SBN_ACT_RELU,
@@ -400,11 +445,8 @@ def main():
     t_cmp = total_flops / (PEAK_MFMA_F32_TFLOPS * 1e12)
     t_mem = sum(bytes_alg) / (PEAK_HBM_GBS * 1e9)
     traffic = None
-    tf = os.path.join(ROOT, "profiles", "conv1x1_pw13_b64_rho30_traffic.txt")
-    if os.path.exists(tf) and a.sparsity == 30 and a.go == 4 and B == 64:
-        for line in open(tf):
-            if line.startswith("traffic_bytes_per_launch="):
-                traffic = float(line.split("=")[1])
+    if a.sparsity == 30 and a.go == 4 and B == 64:
+        traffic = profiled_traffic("conv1x1_pw13_b64_rho30_traffic.txt")
     if t_cmp >= t_mem:
         roof = dict(bound="mfma", achieved=round(total_flops / n_launch / avg_launch_s / 1e12, 3),
                     peak=PEAK_MFMA_F32_TFLOPS, unit="TFLOP/s")
