@@ -12,6 +12,8 @@ Contents, each following the passage it cites:
   * filter / channel rearrangement and its objective (Section 3.4)
   * the layer itself: dense direct convolution on masked weights, via the C
     oracle in sbn_oracle.c                         (Section 3.1; Algorithm 1 result)
+  * 3:9 pattern group pruning of depthwise 3x3 kernels (Section 3.2, DwConv3x3;
+    Algorithm 2's PatternInfo)
 
 Pinned by tests/test_oracle_*.py against brute force, library routines,
 closed forms and the paper's printed FLOP totals.  Parity unpinned: quality of
@@ -338,3 +340,75 @@ def sparse_conv_reference(x_perm: np.ndarray, w: np.ndarray, mask: Optional[np.n
         if perm_out is not None:
             bp = bp[np.asarray(perm_out, dtype=np.int64)]
     return conv_nhwc(x_perm, wt, bp, stride=stride, pad=pad, act=act)
+
+
+# ----------------------------------------------------------------------------
+# Section 3.2, DwConv3x3: 3:9 pattern group pruning.  Every kernel loses three
+# weights, one per row, each taken from the first or the third column: 2^3
+# patterns.  go consecutive channels (16; a remainder forms groups of 8 or 4)
+# share one pattern, the one that keeps the largest l1-norm.  A group may be
+# left dense (Section 3.3's "full-1" pattern); which groups is the caller's
+# choice.
+# ----------------------------------------------------------------------------
+
+DW_PATTERN_DENSE = 8
+
+
+def dw_pattern_mask(pid: int) -> np.ndarray:
+    """uint8 [3][3] keep-mask of pattern pid: bit r of pid set -> row r loses its THIRD column,
+    clear -> its FIRST column; DW_PATTERN_DENSE keeps everything."""
+    m = np.ones((3, 3), dtype=np.uint8)
+    if pid == DW_PATTERN_DENSE:
+        return m
+    assert 0 <= pid < 8
+    for r in range(3):
+        m[r, 2 if (pid >> r) & 1 else 0] = 0
+    return m
+
+
+def dw_pattern_groups(c: int, go: int = 16) -> List[Tuple[int, int]]:
+    """(first channel, size) of every pattern group: as many groups of go as fit, then the
+    remainder in groups of 8 and 4 (Section 3.3); c must be a multiple of 4."""
+    assert c % 4 == 0 and go in (4, 8, 16)
+    out, pos = [], 0
+    while c - pos >= go:
+        out.append((pos, go))
+        pos += go
+    for g in (8, 4):
+        while g < go and c - pos >= g:
+            out.append((pos, g))
+            pos += g
+    assert pos == c
+    return out
+
+
+def dw_pattern_select(w: np.ndarray, go: int = 16, dense_groups: Sequence[int] = ()) -> np.ndarray:
+    """Pattern id per group of w[C][3][3]: the pattern with the largest kept l1-norm over the
+    group's kernels (fp64 sums in channel, row, column order; ties -> the lowest id)."""
+    ids = []
+    for gidx, (c0, n) in enumerate(dw_pattern_groups(w.shape[0], go)):
+        if gidx in dense_groups:
+            ids.append(DW_PATTERN_DENSE)
+            continue
+        best, best_id = -1.0, 0
+        for pid in range(8):
+            m = dw_pattern_mask(pid)
+            tot = 0.0
+            for ch in range(c0, c0 + n):
+                for r in range(3):
+                    for col in range(3):
+                        if m[r, col]:
+                            tot += abs(float(w[ch, r, col]))
+            if tot > best:
+                best, best_id = tot, pid
+        ids.append(best_id)
+    return np.array(ids, dtype=np.uint8)
+
+
+def dw_pattern_apply(w: np.ndarray, ids: Sequence[int], go: int = 16) -> np.ndarray:
+    """W (.) M for the depthwise layer: a select, removed weights become +0.0."""
+    out = w.copy()
+    for (c0, n), pid in zip(dw_pattern_groups(w.shape[0], go), ids):
+        m = dw_pattern_mask(int(pid)).astype(bool)
+        out[c0:c0 + n][:, ~m] = 0.0
+    return out

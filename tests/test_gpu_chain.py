@@ -221,3 +221,38 @@ def test_stem_must_come_first():
     with pytest.raises(S.SbnError) as ei:
         S.sbn_chain_create([S.sparse_item(a), S.stem_item(W.he_weights(9701, 8, 3, 3, 4))])
     assert ei.value.code == -2
+
+
+def test_chain_replays_in_a_hip_graph():
+    """Run calls neither allocate nor synchronise, so a caller may capture them in a HIP graph.
+    The captured chain is replayed several times on new inputs, with eager work and
+    synchronisations between the replays, and every replay must equal the eager result bit for bit."""
+    chans, strides = [16, 32, 64, 32], [1, 2, 1]
+    n, hw = 2, 12
+    items, _ = build_stack(chans, hw, n, 50, 9300, strides)
+    items.append(S.avgpool_item())
+    chain = S.sbn_chain_create(items)
+    oh, ow, oc = S.sbn_chain_output_shape(chain, n, hw, hw)
+    ws = torch.empty(S.sbn_chain_workspace(chain, n, hw, hw) // 4, device="cuda")
+    ws_eager = torch.empty_like(ws)
+    xd = torch.zeros((n, hw, hw, chans[0]), device="cuda")
+    yd = torch.zeros((n, oh, ow, oc), device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        S.sbn_pointwise_chain(chain, xd, yd, n, hw, hw, ws, stream=side)          # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        S.sbn_pointwise_chain(chain, xd, yd, n, hw, hw, ws, stream=side)
+    for rep in range(4):
+        x = torch.from_numpy(W.uniform_activation(9400 + rep, (n, hw, hw, chans[0]))).cuda()
+        y_eager = torch.full((n, oh, ow, oc), float("nan"), device="cuda")
+        S.sbn_pointwise_chain(chain, x, y_eager, n, hw, hw, ws_eager)
+        torch.cuda.synchronize()
+        xd.copy_(x)
+        yd.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(yd, y_eager), f"replay {rep} differs from the eager run"
