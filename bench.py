@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--streams", type=int, default=4,
                     help="HIP streams the 13 independent layers of a step are spread over (1 = strictly serial)")
     ap.add_argument("--no-dense", action="store_true", help="skip the all-groups-kept comparison run")
+    ap.add_argument("--dw-pattern", action="store_true",
+                    help="mobilenet workload: 3:9 pattern-prune the depthwise layers (groups of 16 channels)")
     return ap.parse_args()
 
 
@@ -92,12 +94,13 @@ def build_layers(S, W, batch, pct, go, rearrange):
     return tens, perms, packed, (time.perf_counter() - t0) * 1e3
 
 
-def build_mobilenet_chain(S, W, pct, go=4, seed=4000, max_iters=300):
+def build_mobilenet_chain(S, W, pct, go=4, seed=4000, max_iters=300, dw_pattern=False):
     """Config 4: the whole MobileNet-v1 as one chain.  Pointwise layers are rearranged over
     the whole network (a layer's filter order is the next layer's channel order; the depthwise
     layers in between follow it), pruned by block magnitude and packed; stem, depthwise layers
-    and the classifier stay dense.  Returns (chain, meta) where meta describes every item for
-    the oracle."""
+    and the classifier stay dense; with dw_pattern the depthwise layers are 3:9 pattern pruned in
+    groups of 16 channels (of the order they run in).  Returns (chain, meta) where meta
+    describes every item for the oracle."""
     import numpy as np
     t = W.mobilenet_v1_tensors(seed)
     n = len(t["pw"])
@@ -111,8 +114,12 @@ def build_mobilenet_chain(S, W, pct, go=4, seed=4000, max_iters=300):
     pin = None
     for i in range(n):
         d = W.MOBILENET_V1_DW[i]
-        items.append(S.dw_item(t["dw"][i]["w"], t["dw"][i]["bias"], stride=d.stride, act=S.SBN_ACT_RELU))
-        meta.append(dict(kind="dw", w=t["dw"][i]["w"], b=t["dw"][i]["bias"], stride=d.stride, order=pin))
+        pat = None
+        if dw_pattern:
+            dw_run = t["dw"][i]["w"] if pin is None else t["dw"][i]["w"][pin]
+            pat = S.sbn_dw_pattern_select(np.ascontiguousarray(dw_run), 16)
+        items.append(S.dw_item(t["dw"][i]["w"], t["dw"][i]["bias"], stride=d.stride, act=S.SBN_ACT_RELU, pattern=pat))
+        meta.append(dict(kind="dw", w=t["dw"][i]["w"], b=t["dw"][i]["bias"], stride=d.stride, order=pin, pattern=pat))
         w, b = t["pw"][i]["w"], t["pw"][i]["bias"]
         wp = w[perms[i]] if pin is None else w[perms[i]][..., pin]
         mask = S.sbn_prune_magnitude(np.ascontiguousarray(wp), S.SBN_CONV1X1, go, 4, pct)
@@ -178,7 +185,7 @@ def run_mobilenet(a, torch, S, W):
     """Config 4: whole MobileNet-v1 forward as one chain on one stream (layers depend on each other)."""
     B, pct = a.batch, 50 if a.sparsity == 30 else a.sparsity
     t0 = time.perf_counter()
-    chain, meta = build_mobilenet_chain(S, W, pct, go=a.go)
+    chain, meta = build_mobilenet_chain(S, W, pct, go=a.go, dw_pattern=a.dw_pattern)
     pack_ms = (time.perf_counter() - t0) * 1e3
     hw = W.STEM["hw_in"]
     g = torch.Generator(device="cuda").manual_seed(4000)
@@ -201,7 +208,8 @@ def run_mobilenet(a, torch, S, W):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"MobileNet-v1 forward, batch {B}, 224x224x3 fp32, sparse pointwise layers "
                                f"({pct}% group sparsity, go={a.go} gi=4, rearranged) chained with dense stem, "
-                               f"depthwise 3x3 + ReLU, average pool and classifier", "batch": B,
+                               f"{'3:9 pattern-pruned ' if a.dw_pattern else ''}depthwise 3x3 + ReLU, average pool "
+                               f"and classifier", "batch": B,
                    "sparsity_percent": pct},
         "roofline": {"bound": "hbm", "achieved": round(act_bytes / (ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
                      "unit": "GB/s", "frac": round(act_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None,

@@ -102,6 +102,33 @@ int sbn_retained_l1(const float* w_permuted, int kind, int c_in, int c_out, int 
                     int sparsity_percent, double* objective_out);
 
 /*
+ * 3:9 pattern group pruning of a depthwise 3x3 layer (Section 3.2, DwConv3x3;
+ * Algorithm 2's PatternInfo).  Every kernel loses three weights, one per row,
+ * each from the first or the third column: pattern id = 3 bits, bit r set
+ * means row r loses its THIRD column, clear its FIRST.  `go` consecutive
+ * channels (4, 8 or 16; the paper uses 16) share a pattern; channels left over
+ * form groups of 8 and then 4 (Section 3.3).  SBN_DW_PATTERN_DENSE marks a
+ * group that keeps all nine weights (the "full-1" pattern).
+ *
+ * sbn_dw_pattern_groups: number of groups for c channels (c % 4 == 0) and,
+ * if group_start is not NULL, the first channel of every group plus c at the
+ * end (int [*n_groups_out + 1], caller-allocated; c/4 + 1 entries always fit).
+ *
+ * sbn_dw_pattern_select: for w (host [c][3][3], in the channel order the layer
+ * runs in) writes to pattern_out (uint8 [n_groups]) the pattern that keeps
+ * the largest l1-norm over each group's kernels (fp64 sums in channel, row,
+ * column order; ties -> the lowest id).  keep_dense (uint8 [n_groups] or NULL):
+ * nonzero leaves that group dense.
+ *
+ * sbn_dw_pattern_apply: w_out = W (.) M as a select (removed weights +0.0,
+ * kept ones bit for bit); w_out may equal w.
+ */
+#define SBN_DW_PATTERN_DENSE 8
+int sbn_dw_pattern_groups(int c, int go, int* n_groups_out, int* group_start);
+int sbn_dw_pattern_select(const float* w, int c, int go, const uint8_t* keep_dense, uint8_t* pattern_out);
+int sbn_dw_pattern_apply(const float* w, int c, int go, const uint8_t* pattern, float* w_out);
+
+/*
  * Whole-network rearrangement for a chain of layers (Section 3.4).
  * layers[l].w / c_in / c_out / go / gi / kind are read (mask, bias, perms are
  * ignored).  parent[l] is the index of the layer whose output feeds layer l,
@@ -189,7 +216,7 @@ int sbn_conv3x3_sparse(const sbn_packed_t* p, const float* x, float* y,
  * stay in rearranged channel order between layers; Section 3.5 engine).
  */
 #define SBN_ITEM_SPARSE  1   /* a packed 1x1 or 3x3 layer                                 */
-#define SBN_ITEM_DW3X3   2   /* dense depthwise 3x3, pad 1, + bias + act                  */
+#define SBN_ITEM_DW3X3   2   /* depthwise 3x3, pad 1, + bias + act; dense or 3:9 pattern  */
 #define SBN_ITEM_AVGPOOL 3   /* global average over h*w -> 1x1 spatial                    */
 #define SBN_ITEM_STEM3X3 4   /* dense 3x3 conv of a few input channels (network stem),
                                 pad 1, + bias + act; only as the first item of a chain    */
@@ -204,6 +231,10 @@ typedef struct {
                                    SBN_ITEM_STEM3X3: host OHWI [c_out][3][3][c_in]          */
     const float* dw_bias;       /* host [channels] (DW3X3) / [c_out] (STEM3X3) or NULL      */
     int c_out;                  /* SBN_ITEM_STEM3X3: output channels, multiple of 4, <= 64  */
+    const uint8_t* dw_pattern;  /* SBN_ITEM_DW3X3: NULL (dense) or one 3:9 pattern id per
+                                   group of the layer's channels IN THE ORDER IT RUNS IN (the
+                                   rearranged order); the weights are masked accordingly    */
+    int dw_go;                  /* SBN_ITEM_DW3X3 with dw_pattern: group size (4, 8 or 16)   */
 } sbn_chain_item_t;
 
 /*

@@ -45,7 +45,8 @@ class LayerDesc(C.Structure):
 
 class ChainItem(C.Structure):
     _fields_ = [("item", C.c_int), ("packed", C.c_void_p), ("channels", C.c_int), ("stride", C.c_int),
-                ("act", C.c_int), ("dw_w", C.c_void_p), ("dw_bias", C.c_void_p), ("c_out", C.c_int)]
+                ("act", C.c_int), ("dw_w", C.c_void_p), ("dw_bias", C.c_void_p), ("c_out", C.c_int),
+                ("dw_pattern", C.c_void_p), ("dw_go", C.c_int)]
 
 
 # name -> (restype, argtypes): every symbol include/sbn.h declares
@@ -54,6 +55,9 @@ SYMBOLS = {
     "sbn_prune_magnitude": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "sbn_retained_l1": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                   C.POINTER(C.c_double)]),
+    "sbn_dw_pattern_groups": (C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_int), C.c_void_p]),
+    "sbn_dw_pattern_select": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
+    "sbn_dw_pattern_apply": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "sbn_rearrange": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int,
                                 C.c_uint64, C.c_int, C.POINTER(C.c_void_p)]),
     "sbn_pack": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_void_p)]),

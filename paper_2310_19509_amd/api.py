@@ -16,11 +16,13 @@ __all__ = [
     "sbn_export", "sbn_packed_info", "sbn_packed_work", "sbn_free", "sbn_conv1x1_sparse", "sbn_conv3x3_sparse",
     "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_chain_free",
     "sbn_copy_bytes", "dw_item", "sparse_item", "avgpool_item", "stem_item", "SBN_ITEM_STEM3X3",
+    "SBN_DW_PATTERN_DENSE", "sbn_dw_pattern_groups", "sbn_dw_pattern_select", "sbn_dw_pattern_apply",
 ]
 
 SBN_CONV1X1, SBN_CONV3X3 = 1, 3
 SBN_ACT_NONE, SBN_ACT_RELU = 0, 1
 SBN_ITEM_SPARSE, SBN_ITEM_DW3X3, SBN_ITEM_AVGPOOL, SBN_ITEM_STEM3X3 = 1, 2, 3, 4
+SBN_DW_PATTERN_DENSE = 8
 
 
 class SbnError(RuntimeError):
@@ -132,6 +134,38 @@ def sbn_retained_l1(w_permuted, kind: int, go: int, gi: int, sparsity_percent: i
     return out.value
 
 
+def sbn_dw_pattern_groups(c: int, go: int = 16) -> np.ndarray:
+    """First channel of every 3:9 pattern group of a depthwise layer, plus c at the end."""
+    n = C.c_int()
+    start = np.zeros(c // 4 + 2, dtype=np.int32)
+    _check(_lib.lib().sbn_dw_pattern_groups(c, go, C.byref(n), start.ctypes.data))
+    return start[:n.value + 1].copy()
+
+
+def sbn_dw_pattern_select(w, go: int = 16, keep_dense=None) -> np.ndarray:
+    """w [c][3][3] in the order the layer runs in -> uint8 pattern id per group."""
+    w = _f32(w)
+    c = w.shape[0]
+    n = len(sbn_dw_pattern_groups(c, go)) - 1
+    kd = None if keep_dense is None else np.ascontiguousarray(keep_dense, dtype=np.uint8)
+    if kd is not None and kd.shape != (n,):
+        raise ValueError(f"keep_dense must have one entry per group ({n})")
+    out = np.zeros(n, dtype=np.uint8)
+    _check(_lib.lib().sbn_dw_pattern_select(w.ctypes.data, c, go, _ptr(kd), out.ctypes.data))
+    return out
+
+
+def sbn_dw_pattern_apply(w, pattern, go: int = 16) -> np.ndarray:
+    w = _f32(w)
+    c = w.shape[0]
+    pat = np.ascontiguousarray(pattern, dtype=np.uint8)
+    if pat.shape != (len(sbn_dw_pattern_groups(c, go)) - 1,):
+        raise ValueError("pattern must have one id per group")
+    out = np.empty_like(w)
+    _check(_lib.lib().sbn_dw_pattern_apply(w.ctypes.data, c, go, pat.ctypes.data, out.ctypes.data))
+    return out
+
+
 def sbn_rearrange(layers: Sequence[dict], parent: Sequence[int], sparsity_percent: int, seed: int = 0,
                   max_iters: int = 2000, keep_output_order: Optional[Sequence[int]] = None) -> List[np.ndarray]:
     """layers: dicts with kind, w, go, gi.  Returns one filter permutation per layer."""
@@ -217,8 +251,12 @@ def sparse_item(p: Packed) -> dict:
     return dict(item=SBN_ITEM_SPARSE, packed=p)
 
 
-def dw_item(w, bias=None, stride: int = 1, act: int = SBN_ACT_RELU) -> dict:
-    return dict(item=SBN_ITEM_DW3X3, w=_f32(w), bias=None if bias is None else _f32(bias), stride=stride, act=act)
+def dw_item(w, bias=None, stride: int = 1, act: int = SBN_ACT_RELU, pattern=None, go: int = 16) -> dict:
+    """Depthwise 3x3 item; pattern: one 3:9 pattern id per group of the channels in the order the
+    layer runs in (None = dense)."""
+    pat = None if pattern is None else np.ascontiguousarray(pattern, dtype=np.uint8)
+    return dict(item=SBN_ITEM_DW3X3, w=_f32(w), bias=None if bias is None else _f32(bias), stride=stride, act=act,
+                pattern=pat, go=go)
 
 
 def stem_item(w_ohwi, bias=None, stride: int = 2, act: int = SBN_ACT_RELU) -> dict:
@@ -253,6 +291,12 @@ def sbn_chain_create(items: Sequence[dict], device: int = 0) -> Chain:
             arr[i].act = it["act"]
             arr[i].dw_w = it["w"].ctypes.data
             arr[i].dw_bias = _ptr(it["bias"])
+            if it.get("pattern") is not None:
+                n_groups = len(sbn_dw_pattern_groups(it["w"].shape[0], it["go"])) - 1
+                if it["pattern"].shape != (n_groups,):
+                    raise ValueError(f"chain item {i}: pattern must have one id per group ({n_groups})")
+                arr[i].dw_pattern = it["pattern"].ctypes.data
+                arr[i].dw_go = it["go"]
             keep.append(it)
     out = C.c_void_p()
     _check(_lib.lib().sbn_chain_create(arr, n, device, C.byref(out)))

@@ -115,6 +115,15 @@ int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn
                 return fail(SBN_EINVAL, "chain item %d: bad depthwise description (channels must be a positive multiple of 4, stride 1 or 2)", i);
             }
             if (cur_c >= 0 && s.channels != cur_c) { delete c; return fail(SBN_ESHAPE, "chain item %d has %d channels, previous item writes %d", i, s.channels, cur_c); }
+            if (s.dw_pattern) {
+                std::vector<int> st;
+                if (int rc = dw_group_starts(s.channels, s.dw_go, st)) { delete c; return rc; }
+                for (size_t g = 0; g + 1 < st.size(); ++g)
+                    if (s.dw_pattern[g] > SBN_DW_PATTERN_DENSE) {
+                        delete c;
+                        return fail(SBN_EINVAL, "chain item %d: pattern id %d of group %zu is not in 0..8", i, s.dw_pattern[g], g);
+                    }
+            }
             if (cur_c < 0) c->c_in = s.channels;
             it.channels = s.channels;
             it.stride = s.stride;
@@ -178,9 +187,22 @@ int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn
             }
             if (it.item != SBN_ITEM_DW3X3) continue;
             const int ch_n = it.channels;
+            // 3:9 pattern groups are formed over the channels in the order the layer runs in; the
+            // masked weights go through the dense kernel: the layer is bound by HBM, not by its taps
+            std::vector<uint8_t> pat_of_channel((size_t)ch_n, (uint8_t)SBN_DW_PATTERN_DENSE);
+            if (items[i].dw_pattern) {
+                std::vector<int> st;
+                (void)dw_group_starts(ch_n, items[i].dw_go, st);
+                for (size_t g = 0; g + 1 < st.size(); ++g)
+                    for (int ch = st[g]; ch < st[g + 1]; ++ch) pat_of_channel[(size_t)ch] = items[i].dw_pattern[g];
+            }
             for (int ch = 0; ch < ch_n; ++ch) {
                 const int src = ord.empty() ? ch : ord[(size_t)ch];
-                for (int t = 0; t < 9; ++t) host[off + (size_t)t * ch_n + ch] = items[i].dw_w[(size_t)src * 9 + t];
+                const int pid = pat_of_channel[(size_t)ch];
+                for (int t = 0; t < 9; ++t) {
+                    const bool gone = pid != SBN_DW_PATTERN_DENSE && t % 3 == ((pid >> (t / 3)) & 1 ? 2 : 0);
+                    host[off + (size_t)t * ch_n + ch] = gone ? 0.0f : items[i].dw_w[(size_t)src * 9 + t];
+                }
                 host[off + (size_t)9 * ch_n + ch] = items[i].dw_bias ? items[i].dw_bias[src] : 0.0f;
             }
             it.d_w = blob + off;

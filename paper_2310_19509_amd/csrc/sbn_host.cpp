@@ -308,6 +308,84 @@ int sbn_retained_l1(const float* w, int kind, int c_in, int c_out, int go, int g
     return SBN_OK;
 }
 
+// ---- 3:9 pattern group pruning of depthwise kernels (Section 3.2, DwConv3x3)
+
+extern "C++" {
+namespace sbn {
+int dw_group_starts(int c, int go, std::vector<int>& start)
+{
+    if (c <= 0 || c % 4) return fail(SBN_ESHAPE, "depthwise pattern pruning needs a positive multiple of 4 channels (got %d)", c);
+    if (go != 4 && go != 8 && go != 16) return fail(SBN_EINVAL, "depthwise pattern group size must be 4, 8 or 16 (got %d)", go);
+    start.clear();
+    int pos = 0;
+    for (; c - pos >= go; pos += go) start.push_back(pos);
+    for (int g = 8; g >= 4; g /= 2)
+        for (; g < go && c - pos >= g; pos += g) start.push_back(pos);
+    start.push_back(c);
+    return SBN_OK;
+}
+}  // namespace sbn
+}  // extern "C++"
+
+int sbn_dw_pattern_groups(int c, int go, int* n_groups_out, int* group_start)
+{
+    clear_error();
+    if (!n_groups_out) return fail(SBN_EINVAL, "sbn_dw_pattern_groups: NULL pointer");
+    std::vector<int> st;
+    if (int rc = sbn::dw_group_starts(c, go, st)) return rc;
+    *n_groups_out = (int)st.size() - 1;
+    if (group_start) std::copy(st.begin(), st.end(), group_start);
+    return SBN_OK;
+}
+
+int sbn_dw_pattern_select(const float* w, int c, int go, const uint8_t* keep_dense, uint8_t* pattern_out)
+{
+    clear_error();
+    if (!w || !pattern_out) return fail(SBN_EINVAL, "sbn_dw_pattern_select: NULL pointer");
+    std::vector<int> st;
+    if (int rc = sbn::dw_group_starts(c, go, st)) return rc;
+    for (size_t g = 0; g + 1 < st.size(); ++g) {
+        if (keep_dense && keep_dense[g]) {
+            pattern_out[g] = SBN_DW_PATTERN_DENSE;
+            continue;
+        }
+        double best = -1.0;
+        int best_id = 0;
+        for (int pid = 0; pid < 8; ++pid) {
+            double tot = 0.0;
+            for (int ch = st[g]; ch < st[g + 1]; ++ch)
+                for (int r = 0; r < 3; ++r) {
+                    const int gone = (pid >> r) & 1 ? 2 : 0;
+                    for (int col = 0; col < 3; ++col)
+                        if (col != gone) tot += std::fabs((double)w[(size_t)ch * 9 + r * 3 + col]);
+                }
+            if (tot > best) best = tot, best_id = pid;
+        }
+        pattern_out[g] = (uint8_t)best_id;
+    }
+    return SBN_OK;
+}
+
+int sbn_dw_pattern_apply(const float* w, int c, int go, const uint8_t* pattern, float* w_out)
+{
+    clear_error();
+    if (!w || !pattern || !w_out) return fail(SBN_EINVAL, "sbn_dw_pattern_apply: NULL pointer");
+    std::vector<int> st;
+    if (int rc = sbn::dw_group_starts(c, go, st)) return rc;
+    for (size_t g = 0; g + 1 < st.size(); ++g)
+        if (pattern[g] > SBN_DW_PATTERN_DENSE) return fail(SBN_EINVAL, "pattern id %d of group %zu is not in 0..8", pattern[g], g);
+    for (size_t g = 0; g + 1 < st.size(); ++g)
+        for (int ch = st[g]; ch < st[g + 1]; ++ch)
+            for (int r = 0; r < 3; ++r) {
+                const int gone = pattern[g] == SBN_DW_PATTERN_DENSE ? -1 : (pattern[g] >> r) & 1 ? 2 : 0;
+                for (int col = 0; col < 3; ++col) {
+                    const size_t i = (size_t)ch * 9 + r * 3 + col;
+                    w_out[i] = col == gone ? 0.0f : w[i];
+                }
+            }
+    return SBN_OK;
+}
+
 int sbn_rearrange(const sbn_layer_desc_t* layers, int n_layers, const int* parent, const int* keep_output_order,
                   int pct, uint64_t seed, int max_iters, int32_t* const* perm_out)
 {

@@ -15,6 +15,7 @@ namespace sbn {
 // ---- error reporting -------------------------------------------------------
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();
+int dw_group_starts(int c, int go, std::vector<int>& start);   // pattern groups of a depthwise layer (+ c at the end)
 
 // ---- device-side layout ----------------------------------------------------
 // The canonical rows (one per output group of `go` filters) are regrouped for

@@ -256,3 +256,35 @@ def test_chain_replays_in_a_hip_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(yd, y_eager), f"replay {rep} differs from the eager run"
+
+
+@pytest.mark.parametrize("c,hw,stride,go", [(32, 14, 1, 16), (40, 9, 2, 16), (28, 7, 1, 16), (24, 11, 1, 8)])
+def test_depthwise_layer_with_3_9_pattern_groups(c, hw, stride, go):
+    """A 3:9 pattern-pruned depthwise layer (Section 3.2, DwConv3x3) behind a rearranged pointwise
+    layer: the pattern groups are formed over the channels in the order the layer runs in, and the
+    result must be the oracle's dense depthwise convolution of the select-masked weights."""
+    n, c0 = 2, 16
+    w1 = W.he_weights(9500, c, 1, 1, c0)
+    perm = S.sbn_rearrange([dict(kind=S.SBN_CONV1X1, w=w1, go=4, gi=4)], [-1], 50, seed=9500, max_iters=200)[0]
+    mask = S.sbn_prune_magnitude(R.permute_weights(w1, perm, None), S.SBN_CONV1X1, 4, 4, 50)
+    p1 = S.sbn_pack(S.SBN_CONV1X1, w1, 4, 4, mask=mask, perm_out=perm, act=S.SBN_ACT_RELU)
+    dw_w = W.normal_weights(9501, (c, 3, 3), 0.4)
+    dw_b = W.small_bias(9502, c)
+    n_groups = len(R.dw_pattern_groups(c, go))
+    keep_dense = np.zeros(n_groups, np.uint8)
+    keep_dense[-1] = 1 if n_groups > 1 else 0
+    pattern = S.sbn_dw_pattern_select(dw_w[perm], go, keep_dense=keep_dense)       # on the order it runs in
+    assert pattern.tolist() == R.dw_pattern_select(dw_w[perm], go, dense_groups=tuple(np.nonzero(keep_dense)[0])).tolist()
+    chain = S.sbn_chain_create([S.sparse_item(p1),
+                                S.dw_item(dw_w, dw_b, stride=stride, act=S.SBN_ACT_RELU, pattern=pattern, go=go)])
+    oh, ow, oc = S.sbn_chain_output_shape(chain, n, hw, hw)
+    ws = torch.empty(S.sbn_chain_workspace(chain, n, hw, hw) // 4, device="cuda")
+    x = W.uniform_activation(9503, (n, hw, hw, c0))
+    mid = torch.empty((n, hw, hw, c), device="cuda")
+    yd = torch.full((n, oh, ow, oc), float("nan"), device="cuda")
+    S.sbn_pointwise_chain(chain, torch.from_numpy(x).cuda(), yd, n, hw, hw, ws, layer_outputs=[mid, None])
+    torch.cuda.synchronize()
+    wm = R.dw_pattern_apply(dw_w[perm], pattern, go)
+    assert (wm != 0).sum() < dw_w.size                                              # something was pruned
+    y_ref, bound = R.dwconv3x3_nhwc(mid.cpu().numpy(), wm, dw_b[perm], stride=stride, act=R.ACT_RELU)
+    assert_within_bound(yd.cpu().numpy(), y_ref, bound, "pattern-pruned depthwise layer")

@@ -178,3 +178,42 @@ def test_rearrange_errors():
     _err(lambda: S.sbn_rearrange(layers, [-1, 0], 150), -1)
     bad = [layers[0], dict(kind=S.SBN_CONV1X1, w=W.he_weights(372, 16, 1, 1, 24), go=4, gi=4)]
     _err(lambda: S.sbn_rearrange(bad, [-1, 0], 50), -2)
+
+
+# ---- 3:9 pattern group pruning of depthwise kernels (Section 3.2, DwConv3x3)
+
+@pytest.mark.parametrize("c,go", [(32, 16), (24, 16), (28, 16), (12, 16), (24, 8), (4, 16), (40, 4)])
+def test_dw_pattern_groups_match_the_oracle(c, go):
+    want = R.dw_pattern_groups(c, go)
+    got = S.sbn_dw_pattern_groups(c, go)
+    assert got.tolist() == [g[0] for g in want] + [c]
+
+
+@pytest.mark.parametrize("c,go,seed", [(64, 16, 1), (40, 16, 2), (28, 16, 3), (32, 8, 4), (16, 4, 5)])
+def test_dw_pattern_select_and_apply_bit_exact(c, go, seed):
+    w = W.normal_weights(7700 + seed, (c, 3, 3), 0.4)
+    w[1, 2, 0] = -0.0
+    n_groups = len(R.dw_pattern_groups(c, go))
+    dense = (1,) if n_groups > 1 else ()
+    kd = np.zeros(n_groups, np.uint8)
+    kd[list(dense)] = 1
+    want = R.dw_pattern_select(w, go, dense_groups=dense)
+    got = S.sbn_dw_pattern_select(w, go, keep_dense=kd)
+    assert got.tolist() == want.tolist()
+    wm = S.sbn_dw_pattern_apply(w, got, go)
+    assert np.array_equal(wm.view(np.uint32), R.dw_pattern_apply(w, want, go).view(np.uint32))
+
+
+def test_dw_pattern_ties_take_the_lowest_id():
+    w = np.ones((16, 3, 3), dtype=np.float32)
+    assert S.sbn_dw_pattern_select(w, 16).tolist() == [0] == R.dw_pattern_select(w, 16).tolist()
+
+
+def test_dw_pattern_errors():
+    w = np.zeros((6, 3, 3), np.float32)
+    with pytest.raises(S.SbnError):
+        S.sbn_dw_pattern_select(w, 16)                       # 6 channels: not a multiple of 4
+    with pytest.raises(S.SbnError):
+        S.sbn_dw_pattern_groups(16, 5)                       # group size
+    with pytest.raises(S.SbnError):
+        S.sbn_dw_pattern_apply(np.zeros((16, 3, 3), np.float32), np.array([9], np.uint8), 16)
