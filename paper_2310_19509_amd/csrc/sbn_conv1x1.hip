@@ -307,7 +307,8 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
 {
     hipStream_t st = (hipStream_t)stream;
     const int K = p->c_in;
-    static const int force = getenv("SBN_K1_VARIANT") ? atoi(getenv("SBN_K1_VARIANT")) : 0;   // benchmarking override
+    const char* forced = getenv("SBN_K1_VARIANT");      // testing / benchmarking override, read per launch
+    const int force = forced ? atoi(forced) : 0;
     if (K % 4) {
         if (K <= 32) return launch<1, 2, 32, false, false>(p, x, y, M, st);
         if (K <= 64) return launch<1, 2, 64, false, false>(p, x, y, M, st);

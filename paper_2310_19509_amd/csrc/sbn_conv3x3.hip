@@ -360,11 +360,8 @@ int launch_conv3x3(const sbn_packed* p, const float* x, float* y, int n, int h, 
     if (p->stride == 2) return launch<2, 1, false>(p, x, y, n, h, w, st);
     // Variant: two pixels per lane unless the 16-wide tiles would be mostly empty or would leave
     // the chip short of waves; with at most about two waves per SIMD the entry-ahead variant.
-    static const int forced = [] {
-        const char* e = getenv("SBN_K3_VARIANT");
-        return e ? atoi(e) : 0;
-    }();
-    int variant = forced;
+    const char* forced = getenv("SBN_K3_VARIANT");      // testing / benchmarking override, read per launch
+    int variant = forced ? atoi(forced) : 0;
     if (!variant) {
         const long long col_tiles = (p->dev.n_bundles + 3) / 4;
         const long long wg1 = (long long)n * ((w + 7) / 8) * ((h + 7) / 8) * col_tiles;

@@ -45,11 +45,30 @@ CASES = [
     (1, 12, 12, 128, 128, 4, 4, 2, 70, True, True, False),   # stride 2, several chunks
     (1, 5, 5, 16, 16, 4, 4, 1, 100, True, True, False),      # everything pruned
     (1, 8, 8, 32, 16, 4, 4, 1, 90, True, False, False),      # empty rows
+    (3, 19, 33, 72, 80, 4, 4, 1, 60, True, True, True),      # three 16-wide tiles with a ragged one, odd height
+    (2, 8, 16, 36, 20, 4, 4, 1, 40, True, False, False),     # exactly one 16-wide tile; K, N not multiples of 16
 ]
 
 
+@pytest.fixture
+def kernel_variant(monkeypatch):
+    """Forces one form of the stride-1 kernel (the library reads the variable at every launch):
+    1 = one pixel per lane, row-ahead; 2 = two pixels per lane; 3 = one pixel per lane, entry-ahead."""
+    def force(v):
+        if v:
+            monkeypatch.setenv("SBN_K3_VARIANT", str(v))
+        else:
+            monkeypatch.delenv("SBN_K3_VARIANT", raising=False)
+    yield force
+    monkeypatch.delenv("SBN_K3_VARIANT", raising=False)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 @pytest.mark.parametrize("n,h,w,K,N,go,gi,stride,pct,use_bias,relu,perms", CASES)
-def test_shapes(n, h, w, K, N, go, gi, stride, pct, use_bias, relu, perms):
+def test_shapes(n, h, w, K, N, go, gi, stride, pct, use_bias, relu, perms, variant, kernel_variant):
+    if variant and stride != 1:
+        pytest.skip("stride 2 has one form")
+    kernel_variant(variant)
     seed = 8000 + 3 * K + N + go + gi + pct + stride
     wt = W.he_weights(seed, N, 3, 3, K)
     b = W.small_bias(seed + 1, N) * 20 if use_bias else None
