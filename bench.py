@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--streams", type=int, default=4,
                     help="HIP streams the 13 independent layers of a step are spread over (1 = strictly serial)")
     ap.add_argument("--no-dense", action="store_true", help="skip the all-groups-kept comparison run")
+    ap.add_argument("--graph", action="store_true",
+                    help="mobilenet workload: capture the chain in a HIP graph once and time its replays")
     ap.add_argument("--dw-pattern", action="store_true",
                     help="mobilenet workload: 3:9 pattern-prune the depthwise layers (groups of 16 channels)")
     return ap.parse_args()
@@ -192,7 +194,19 @@ def run_mobilenet(a, torch, S, W):
     x = torch.rand((B, hw, hw, 3), device="cuda", generator=g) * 2 - 1
     y = torch.empty((B, 1, 1, 1000), device="cuda")
     ws = torch.empty(S.sbn_chain_workspace(chain, B, hw, hw) // 4, device="cuda")
-    ms = time_steps(torch, lambda: S.sbn_pointwise_chain(chain, x, y, B, hw, hw, ws), a.steps, a.warmup)
+    if a.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            S.sbn_pointwise_chain(chain, x, y, B, hw, hw, ws, stream=side)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            S.sbn_pointwise_chain(chain, x, y, B, hw, hw, ws, stream=side)
+        ms = time_steps(torch, graph.replay, a.steps, a.warmup)
+    else:
+        ms = time_steps(torch, lambda: S.sbn_pointwise_chain(chain, x, y, B, hw, hw, ws), a.steps, a.warmup)
     macs = W.mobilenet_v1_macs()
     nz = 0.0
     for m, L in zip([m for m in meta if m["kind"] == "pw"][:13], W.MOBILENET_V1_PW):
@@ -215,6 +229,7 @@ def run_mobilenet(a, torch, S, W):
                      "unit": "GB/s", "frac": round(act_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None,
                      "kernel": "whole chain (29 launches); activation bytes of every layer read and written once"},
         "extra": {"images_per_s": round(B / (ms * 1e-3), 1), "offline_pack_ms": round(pack_ms, 1),
+                  "launch": "HIP graph replay" if a.graph else "eager, one stream",
                   "pointwise_nonzero_gflop": round(nz / 1e9, 2), "dense_rest_gflop": round(dense_rest / 1e9, 2),
                   "pointwise_mfma_roof_ms": round(t_roof * 1e3, 4),
                   "paper_context": "Snapdragon 855: 32.22 ms dense, 19.68 ms at 50% per image (batch 1)"},

@@ -282,6 +282,146 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
     }
 }
 
+// Few-pixel form.  With few pixels (batch 1, deep layers) the workgroup kernel above leaves most
+// of the chip idle: pixel tiles x column tiles is far below the number of CUs while every wave walks
+// all of c_in serially.  Here a workgroup owns 64 pixels x ONE bundle and its NW waves split the
+// input channels: wave s takes the 32-channel sub-chunks s, s + NW, ...  A wave shares nothing while
+// it works (own activation tile in its own LDS slice, staged through registers one sub-chunk ahead;
+// LDS operations of one wave execute in order, so no barrier is needed); at the end the NW partial
+// results meet in LDS and are added in wave order, which keeps the sum deterministic.
+// Needs c_in % 4 == 0.
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void conv1x1_splitk_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                                 const uint32_t* __restrict__ records,
+                                                                 const uint32_t* __restrict__ woff,
+                                                                 const float* __restrict__ wts,
+                                                                 const float* __restrict__ bias, long long M, int K,
+                                                                 int N, int n_bundles, int n_chunks, int act)
+{
+    constexpr int KC = 32, NS = KC / 4, NWL = NS / 4, XS = KC + 4, NA = 2;
+    constexpr int NL = 8;                                // 16-byte slots per lane and tile
+    __shared__ __attribute__((aligned(16))) float lds_all[NW][64 * XS];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    float* lds = lds_all[wave];
+    const int bundle = blockIdx.x % n_bundles;           // neighbouring workgroups share the pixels
+    const long long pix0 = (long long)(blockIdx.x / n_bundles) * 64;
+
+    v4f acc[1][4][NA];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int a = 0; a < NA; ++a) acc[0][g][a] = (v4f){0.f, 0.f, 0.f, 0.f};
+
+    // ---- activation staging: 8 lanes fetch the 128 bytes of one row, 8 rows per instruction
+    const float* xtile = x + pix0 * K;
+    const int rows_valid = (int)(M - pix0 < 64 ? M - pix0 : 64);
+    const int scol = (lane & 7) * 4;
+    v4f stage_reg[NL];
+    auto issue_x = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int row = i * 8 + (lane >> 3);
+            const float* rp = xtile + (size_t)(row < rows_valid ? row : rows_valid - 1) * K;
+            stage_reg[i] = *(const v4f*)(rp + min(c * KC + scol, K - 4));
+        }
+    };
+    auto write_x = [&]() {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) *(v4f*)(lds + (i * 8 + (lane >> 3)) * XS + scol) = stage_reg[i];
+    };
+    const uint32_t* wo = woff + (size_t)bundle * (n_chunks + 1);
+    const Record<NS>* recs = (const Record<NS>*)__builtin_assume_aligned(records, 4 * NS) + (size_t)bundle * n_chunks;
+    auto load_weights = [&](int c, v4f (&w)[NWL]) {
+        const uint32_t e0 = __builtin_amdgcn_readfirstlane(wo[c]);
+        const v4f* src = (const v4f*)(wts + (size_t)e0 * 64) + lane;
+#pragma unroll
+        for (int q4 = 0; q4 < NWL; ++q4) w[q4] = src[q4 * 64];
+    };
+    const char* lds_lane = (const char*)lds + lane * (XS * 4);
+    auto read_x = [&](uint32_t d, v4f (&xv)[1]) { xv[0] = *(const v4f*)(lds_lane + (d >> 8) * 16); };
+    auto walk = [&](const Record<NS>& r, const v4f (&w)[NWL]) {
+        v4f xa[1], xb[1];
+#define SBN_ENTRY(Q, XC, XN)                                            \
+    if (__builtin_expect(r.d[Q] == 0, 0)) goto walk_done;               \
+    if (Q + 1 < NS) read_x(r.d[(Q + 1) % NS], XN);                      \
+    entry_fma<1, NA, Q>(r.d[Q], w[Q / 4], XC, acc);
+        read_x(r.d[0], xa);
+        SBN_ENTRY(0, xa, xb)
+        SBN_ENTRY(1, xb, xa)
+        SBN_ENTRY(2, xa, xb)
+        SBN_ENTRY(3, xb, xa)
+        SBN_ENTRY(4, xa, xb)
+        SBN_ENTRY(5, xb, xa)
+        SBN_ENTRY(6, xa, xb)
+        SBN_ENTRY(7, xb, xa)
+#undef SBN_ENTRY
+    walk_done:;
+    };
+
+    // this wave's sub-chunks: wave, wave + NW, ...; the next one's loads are in flight while the
+    // current one is multiplied (the last one fetches itself again: loads stay unconditional)
+    if (wave < n_chunks) {
+        v4f w_cur[NWL], w_nxt[NWL];
+        Record<NS> r_cur, r_nxt;
+        issue_x(wave);
+        load_weights(wave, w_cur);
+        r_cur = recs[wave];
+        write_x();
+        for (int c = wave; c < n_chunks; c += NW) {
+            const int cn = c + NW < n_chunks ? c + NW : c;
+            issue_x(cn);
+            load_weights(cn, w_nxt);
+            r_nxt = recs[cn];
+            walk(r_cur, w_cur);
+            write_x();
+#pragma unroll
+            for (int q4 = 0; q4 < NWL; ++q4) w_cur[q4] = w_nxt[q4];
+            r_cur = r_nxt;
+        }
+    }
+
+    // ---- the NW partial results meet in LDS and are added in wave order
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        v4f o = acc[0][g][0];
+#pragma unroll
+        for (int a = 1; a < NA; ++a) o += acc[0][g][a];
+        *(v4f*)(lds + lane * XS + g * 4) = o;
+    }
+    __syncthreads();
+    if (threadIdx.x < 256) {
+        const int row = threadIdx.x >> 2, col = (threadIdx.x & 3) * 4;
+        v4f o = *(const v4f*)(lds_all[0] + row * XS + col);
+#pragma unroll
+        for (int s = 1; s < NW; ++s) o += *(const v4f*)(lds_all[s] + row * XS + col);
+        o += *(const v4f*)(bias + bundle * 16 + col);
+        if (act == SBN_ACT_RELU) {
+            o.x = fmaxf(o.x, 0.f);
+            o.y = fmaxf(o.y, 0.f);
+            o.z = fmaxf(o.z, 0.f);
+            o.w = fmaxf(o.w, 0.f);
+        }
+        const long long pix = pix0 + row;
+        if (pix < M && bundle * 16 + col < N) *(v4f*)(y + pix * N + bundle * 16 + col) = o;
+    }
+}
+
+template <int NW>
+int launch_splitk(const sbn_packed* p, const float* x, float* y, long long M, hipStream_t st)
+{
+    const sbn::DeviceLayout& L = p->dev;
+    const long long n_pix_tiles = (M + 63) / 64;
+    const long long grid = n_pix_tiles * L.n_bundles;
+    if (grid > 0x7FFFFFFFll) return sbn::fail(SBN_EINVAL, "too many pixels for one launch (%lld)", M);
+    hipLaunchKernelGGL((conv1x1_splitk_kernel<NW>), dim3((unsigned)grid), dim3(64 * NW), 0, st, x, y, L.d_records32,
+                       L.d_woff32, L.d_wts, L.d_bias, M, p->c_in, p->c_out, L.n_bundles, L.n_chunks32, p->act);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return sbn::fail(SBN_EHIP, "conv1x1 launch: %s", hipGetErrorString(e));
+    return SBN_OK;
+}
+
 template <int P, int NA, int KC, bool MULTI, bool VEC>
 int launch(const sbn_packed* p, const float* x, float* y, long long M, hipStream_t st)
 {
@@ -319,6 +459,11 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
     if (K <= 32) return p2 ? launch<2, 1, 32, false, true>(p, x, y, M, st) : launch<1, 2, 32, false, true>(p, x, y, M, st);
     if (K <= 64) return p2 ? launch<2, 1, 64, false, true>(p, x, y, M, st) : launch<1, 2, 64, false, true>(p, x, y, M, st);
     int variant = force;
+    // few pixels: less than one workgroup per CU -> one bundle per workgroup, input channels
+    // split over its waves
+    const int n_sub = p->dev.n_chunks32;
+    if (!variant && n_sub >= 4 && ((M + 63) / 64) * ((p->dev.n_bundles + 3) / 4) < 256)
+        variant = n_sub >= 16 ? 516 : n_sub >= 8 ? 508 : 504;
     if (!variant) {
         // 128-pixel tiles with 32-channel chunks halve the per-entry overhead; they pay off
         // when there are still several such tiles per CU (256 CUs)
@@ -330,6 +475,9 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
     case 14: return launch<1, 4, 64, true, true>(p, x, y, M, st);
     case 21: return launch<2, 1, 32, true, true>(p, x, y, M, st);
     case 22: return launch<2, 2, 32, true, true>(p, x, y, M, st);
+    case 504: return launch_splitk<4>(p, x, y, M, st);
+    case 508: return launch_splitk<8>(p, x, y, M, st);
+    case 516: return launch_splitk<16>(p, x, y, M, st);
     default: return launch<1, 2, 64, true, true>(p, x, y, M, st);
     }
 }

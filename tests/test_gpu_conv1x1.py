@@ -70,7 +70,7 @@ def test_shapes(n, h, w, K, N, go, gi, pct, use_bias, relu, perms):
         assert np.array_equal(y, np.broadcast_to(expect, y.shape))
 
 
-@pytest.mark.parametrize("variant", [11, 12, 14, 21, 22])
+@pytest.mark.parametrize("variant", [11, 12, 14, 21, 22, 504, 508, 516])
 @pytest.mark.parametrize("n,h,w,K,N,pct", [(3, 9, 11, 128, 256, 30), (1, 7, 7, 512, 1024, 70), (2, 13, 5, 72, 40, 50),
                                              (1, 20, 20, 320, 64, 0)])
 def test_every_multi_chunk_kernel_form(monkeypatch, variant, n, h, w, K, N, pct):
