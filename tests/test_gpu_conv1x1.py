@@ -212,3 +212,30 @@ def test_same_layer_on_two_streams_and_repeated_launches():
     ref, bound = R.sparse_conv_reference(t["x"], t["w"], mask, 4, 4, bias=t["bias"])
     assert_within_bound(ys[0].cpu().numpy(), ref, bound, "stream 0")
     assert_within_bound(ys[1].cpu().numpy(), ref[::-1], bound[::-1], "stream 1")
+
+
+def test_activations_beyond_4_gib():
+    """17 million pixels x 64 channels: input and output are 4.35 GB each, so byte offsets pass
+    2^32 and pixel*channel indices pass 2^30; sampled pixels from the start, the 4 GiB crossing and
+    the ragged end are checked against the oracle."""
+    K = N = 64
+    m = 17_000_011                                     # not a multiple of the 64-pixel tile
+    free, _ = torch.cuda.mem_get_info()
+    if free < 10 * (1 << 30):
+        pytest.skip("needs 10 GiB of device memory")
+    wt = W.he_weights(7900, N, 1, 1, K)
+    b = W.small_bias(7901, N)
+    mask = S.sbn_prune_magnitude(wt, S.SBN_CONV1X1, 4, 4, 50)
+    p = S.sbn_pack(S.SBN_CONV1X1, wt, 4, 4, mask=mask, bias=b, act=S.SBN_ACT_RELU)
+    g = torch.Generator(device="cuda").manual_seed(7902)
+    xd = torch.rand((m, K), device="cuda", generator=g) * 2 - 1
+    yd = torch.full((m, N), float("nan"), device="cuda")
+    S.sbn_conv1x1_sparse(p, xd, yd, 1, 1, m)
+    torch.cuda.synchronize()
+    cross = (1 << 32) // (4 * K)                       # first pixel whose bytes start beyond 4 GiB
+    rows = np.concatenate([np.arange(0, 200), np.arange(cross - 100, cross + 100), np.arange(m - 300, m)])
+    idx = torch.from_numpy(rows).cuda()
+    xs = xd[idx].cpu().numpy().reshape(1, 1, len(rows), K)
+    ref, bound = R.sparse_conv_reference(xs, wt, mask, 4, 4, bias=b, act=R.ACT_RELU)
+    assert_within_bound(yd[idx].cpu().numpy().reshape(ref.shape), ref, bound, "rows around 4 GiB")
+    assert not torch.isnan(yd[::100003]).any()

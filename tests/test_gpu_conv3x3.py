@@ -118,3 +118,27 @@ def test_resnet50_shapes_batch32_sampled(idx):
         ref, bound = R.sparse_conv_reference(xs, t["w"], mask, 4, 4, bias=t["bias"], stride=1, pad=1,
                                              act=S.SBN_ACT_RELU)
         assert_within_bound(ys, ref, bound, f"resnet shape {idx}")
+
+
+def test_activations_beyond_4_gib():
+    """5400 images of 56x56x64: input and output are 4.3 GB each, so image byte offsets pass 2^32;
+    whole images at the start, around the crossing and at the end are checked against the oracle."""
+    c, hw, n = 64, 56, 5400
+    free, _ = torch.cuda.mem_get_info()
+    if free < 10 * (1 << 30):
+        pytest.skip("needs 10 GiB of device memory")
+    wt = W.he_weights(8900, c, 3, 3, c)
+    b = W.small_bias(8901, c)
+    mask = S.sbn_prune_magnitude(wt, S.SBN_CONV3X3, 4, 4, 70)
+    p = S.sbn_pack(S.SBN_CONV3X3, wt, 4, 4, mask=mask, bias=b, act=S.SBN_ACT_RELU)
+    g = torch.Generator(device="cuda").manual_seed(8902)
+    xd = torch.rand((n, hw, hw, c), device="cuda", generator=g) * 2 - 1
+    yd = torch.full((n, hw, hw, c), float("nan"), device="cuda")
+    S.sbn_conv3x3_sparse(p, xd, yd, n, hw, hw)
+    torch.cuda.synchronize()
+    cross = (1 << 32) // (4 * hw * hw * c)             # the image that straddles 4 GiB
+    imgs = [0, cross - 1, cross, cross + 1, n - 1]
+    idx = torch.tensor(imgs, device="cuda")
+    ref, bound = R.sparse_conv_reference(xd[idx].cpu().numpy(), wt, mask, 4, 4, bias=b, stride=1, pad=1, act=R.ACT_RELU)
+    assert_within_bound(yd[idx].cpu().numpy(), ref, bound, "images around 4 GiB")
+    assert not torch.isnan(yd[::97, ::11, ::13]).any()
