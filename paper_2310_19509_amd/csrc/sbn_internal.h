@@ -59,7 +59,6 @@ struct DeviceLayout {
     uint32_t* d_woff32 = nullptr;
     float* d_wts = nullptr;
     float* d_bias = nullptr;
-    float* d_zeros = nullptr;             // 64 zero floats (source of out-of-image activation slots)
 };
 
 }  // namespace sbn

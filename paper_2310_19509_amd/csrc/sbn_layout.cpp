@@ -107,7 +107,7 @@ int upload_device_layout(sbn_packed* p)
     const size_t b_rec32 = align256(L.records32.size() * sizeof(uint32_t));
     const size_t b_woff32 = align256(L.woff32.size() * sizeof(uint32_t));
     const size_t b_wts = align256((L.wts.size() + kSlots * wstride) * sizeof(float));
-    const size_t b_bias = align256((L.bias_padded.size() + 64) * sizeof(float));   // + a block of zeros
+    const size_t b_bias = align256(L.bias_padded.size() * sizeof(float));
     const size_t total = b_rec + b_woff + b_rec32 + b_woff32 + b_wts + b_bias;
     char* blob = nullptr;
     if ((e = hipMalloc((void**)&blob, total)) != hipSuccess) {
@@ -133,7 +133,6 @@ int upload_device_layout(sbn_packed* p)
     off += b_wts;
     std::memcpy(host.data() + off, L.bias_padded.data(), L.bias_padded.size() * sizeof(float));
     L.d_bias = (float*)(blob + off);
-    L.d_zeros = L.d_bias + L.bias_padded.size();
     e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {
