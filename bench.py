@@ -168,9 +168,16 @@ def cpu_baseline(W, tens, perms, pct, go, batch):
     while t < 8.0 and passes < 8:            # a bounded sample: a few seconds of wall time on all host cores
         dt, df = one_pass(b)
         t, f, passes = t + dt, f + df, passes + 1
+    # the same oracle on one thread, one image (a few seconds): the single-core figure beside it
+    R.set_num_threads(1)
+    try:
+        ts, fs = one_pass(1)
+    finally:
+        R.set_num_threads(threads)
     return dict(value=round(f / t / 1e9, 2), unit="GFLOP/s", cores=threads, kind="oracle",
                 sample=f"{passes} passes of {b} of {batch} images through all 13 layers, {t:.2f} s on {threads} "
-                       f"threads; nonzero FLOPs counted, the oracle itself multiplies every (zeroed) weight in fp64")
+                       f"threads; nonzero FLOPs counted, the oracle itself multiplies every (zeroed) weight in fp64",
+                one_thread_value=round(fs / ts / 1e9, 2), one_thread_sample=f"1 image through all 13 layers, {ts:.2f} s")
 
 
 def time_steps(torch, fn, steps, warmup):
