@@ -23,6 +23,9 @@
  *   - sbn_packed_t / sbn_chain_t are opaque, created by the library and
  *     released by sbn_free / sbn_chain_free.  A chain borrows its packed
  *     layers: free the chain first.
+ *   - Removed blocks are skipped, not multiplied by zero: with finite activations the result is
+ *     that of the dense convolution with W~ (up to fp32 summation order); a NaN or infinity in a
+ *     channel that only removed blocks read may or may not reach the output.
  *   - Single-layer run calls work in PERMUTED channel space: x carries its
  *     channels in perm_in order and y comes out in perm_out order.  That is
  *     what makes the rearrangement free at run time (Section 3.4).
