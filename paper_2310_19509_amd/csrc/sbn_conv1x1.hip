@@ -185,22 +185,33 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
             issue_x(cn);
             load_weights(cn, w_nxt);
             r_nxt = recs[cn];
+            // This chunk's weights were fetched a chunk ago: everything but the loads just issued
+            // has to be complete.  Saying so once here spares a wait in front of every group's
+            // multiplies (the compiler cannot carry that knowledge across the group branches).
+            constexpr int NEW = (VEC ? NL : 4 * NL) + NW;
+            static_assert(NEW < 64, "vmcnt is a 6-bit counter");
+            __builtin_amdgcn_s_waitcnt((NEW & 15) | ((NEW >> 4) << 14) | (7 << 4) | (15 << 8));
         }
 
         if (active) {
             const char* lds_lane = (const char*)xbuf + lane * (XS * 4);
             v4f xa[P], xb[P];
             auto read_x = [&](uint32_t d, v4f (&xv)[P]) {
-                const int off = (d >> 8) * 16;           // kb4 within the chunk: < 16
+                const int off = d >> 8;                  // 16 * kb4 within the chunk
 #pragma unroll
                 for (int p = 0; p < P; ++p) xv[p] = *(const v4f*)(lds_lane + off + p * (64 * XS * 4));
             };
             // Entries are compacted at the front of the record; the first zero
             // descriptor ends the chunk.  Activations run one entry ahead.
+            // One wait per entry, in front of the group tests: LDS reads return in order, so with
+            // at most the P reads of the next entry outstanding this entry's activations have
+            // arrived (the first entry also waits for the record, a scalar load).  Without it the
+            // compiler puts a wait in front of every group's multiplies.
 #define SBN_ENTRY(Q, XC, XN)                                                   \
     if (Q < NS) {                                                              \
         if (__builtin_expect(r_cur.d[Q % NS] == 0, 0)) goto chunk_done;        \
         if (Q + 1 < NS) read_x(r_cur.d[(Q + 1) % NS], XN);                     \
+        __builtin_amdgcn_s_waitcnt(0xC07F | ((Q == 0 || Q + 1 >= NS ? 0 : P) << 8)); \
         entry_fma<P, NA, Q>(r_cur.d[Q % NS], w_cur[(Q / 4) % NW], XC, acc);    \
     }
             read_x(r_cur.d[0], xa);
@@ -340,7 +351,7 @@ __global__ __launch_bounds__(64 * NW) void conv1x1_splitk_kernel(const float* __
         for (int q4 = 0; q4 < NWL; ++q4) w[q4] = src[q4 * 64];
     };
     const char* lds_lane = (const char*)lds + lane * (XS * 4);
-    auto read_x = [&](uint32_t d, v4f (&xv)[1]) { xv[0] = *(const v4f*)(lds_lane + (d >> 8) * 16); };
+    auto read_x = [&](uint32_t d, v4f (&xv)[1]) { xv[0] = *(const v4f*)(lds_lane + (d >> 8)); };
     auto walk = [&](const Record<NS>& r, const v4f (&w)[NWL]) {
         v4f xa[1], xb[1];
 #define SBN_ENTRY(Q, XC, XN)                                            \

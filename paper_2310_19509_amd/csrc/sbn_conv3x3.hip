@@ -201,10 +201,10 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
             auto desc = [&](uint32_t qq) -> uint32_t {
                 return qq < 16 ? (uint32_t)__builtin_amdgcn_readlane((int)dv, (int)qq) : 0u;
             };
-            auto mine = [&](uint32_t d) { return d != 0 && ((d >> 11) & 1u) == h; };
+            auto mine = [&](uint32_t d) { return d != 0 && ((d >> 15) & 1u) == h; };
             // activations under one row of taps of the piece named by descriptor d
             auto load_x = [&](uint32_t d, int ky, v4f (&xr)[NX]) {
-                const int s16 = (int)((d >> 8) & 7u) << 4;
+                const int s16 = (int)((d >> 8) & 0x70u);     // 16 * (piece within the 32-channel sub-chunk)
 #pragma unroll
                 for (int c = 0; c < NX; ++c) {
                     const int j = PX == 1 && STRIDE == 1 ? c : c >> 1;

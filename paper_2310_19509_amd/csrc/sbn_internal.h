@@ -23,7 +23,8 @@ int dw_group_starts(int c, int go, std::vector<int>& start);   // pattern groups
 // A bundle walks the union of its groups' kept 4-channel pieces in ascending
 // channel order; an ENTRY is one such piece.  Per bundle and per chunk of 64
 // input channels there is one fixed-size RECORD of 16 descriptors (64 bytes):
-//     records[bundle][chunk][q] = (kb4_in_chunk << 8) | present_mask   q < n
+//     records[bundle][chunk][q] = (kb4_in_chunk << 12) | present_mask  q < n   (so that
+//                                 descriptor >> 8 is the piece's byte offset in a staged row)
 //                               = 0                                    q >= n
 // kb4_in_chunk = (first channel of the piece - 64*chunk) / 4; bit g of
 // present_mask says that group g of the bundle keeps the piece; n <= 16 is

@@ -64,7 +64,7 @@ void build_device_layout(sbn_packed* p)
         for (int c = 0; c <= L.n_chunks; ++c) wo[c] = (uint32_t)n_entries;
         for (const auto& kv : pos) {
             const int c = kv.first / kSlots, q = fill[(size_t)c]++;
-            L.records[((size_t)b * L.n_chunks + c) * kSlots + q] = ((uint32_t)(kv.first % kSlots) << 8) | kv.second.second;
+            L.records[((size_t)b * L.n_chunks + c) * kSlots + q] = ((uint32_t)(kv.first % kSlots) << 12) | kv.second.second;
             wo[c] = std::min(wo[c], (uint32_t)kv.second.first);
         }
         // empty chunks start where the next non-empty one does
@@ -75,7 +75,7 @@ void build_device_layout(sbn_packed* p)
         for (int c = 0; c <= L.n_chunks32; ++c) wo32[c] = (uint32_t)n_entries;
         for (const auto& kv : pos) {
             const int c = kv.first / 8, q = fill32[(size_t)c]++;
-            L.records32[((size_t)b * L.n_chunks32 + c) * 8 + q] = ((uint32_t)(kv.first % 8) << 8) | kv.second.second;
+            L.records32[((size_t)b * L.n_chunks32 + c) * 8 + q] = ((uint32_t)(kv.first % 8) << 12) | kv.second.second;
             wo32[c] = std::min(wo32[c], (uint32_t)kv.second.first);
         }
         for (int c = L.n_chunks32 - 1; c >= 0; --c) wo32[c] = std::min(wo32[c], wo32[c + 1]);
