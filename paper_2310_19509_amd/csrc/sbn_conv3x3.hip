@@ -47,15 +47,16 @@ __device__ __forceinline__ v4f mfma_bcast(float w, float x, v4f c)
     return __builtin_amdgcn_mfma_f32_4x4x1f32(w, x, c, 4, ABID, 0);
 }
 
-// One row of taps (ky = KY, kx = 0..2) of group G over the lane's PX pixels.  w[t] holds tap t,
-// lane l = [g][ci][co]; x holds the (PX-1)*STRIDE+3 input columns under the pixels.
+// One row of taps (ky = KY, kx = 0..2) of group G over the lane's PX pixels.  w holds the entry's
+// nine taps (WT = 9) or just this row's three (WT = 3), lane l = [g][ci][co]; x holds the
+// (PX-1)*STRIDE+3 input columns under the pixels.
 // PX = 1: acc[G][0/1] are two partial sums of the one pixel; PX = 2: acc[G][p] is pixel p.
-template <int G, int KY, int PX, int STRIDE, int NX>
-__device__ __forceinline__ void row_fma(const float (&w)[9], const v4f (&x)[NX], v4f (&acc)[4][2])
+template <int G, int KY, int PX, int STRIDE, int NX, int WT>
+__device__ __forceinline__ void row_fma(const float (&w)[WT], const v4f (&x)[NX], v4f (&acc)[4][2])
 {
 #pragma unroll
     for (int kx = 0; kx < 3; ++kx) {
-        const float wt = w[KY * 3 + kx];
+        const float wt = w[WT == 9 ? KY * 3 + kx : kx];
         if constexpr (PX == 1) {
             acc[G][0] = mfma_bcast<G * 4 + 0>(wt, x[kx].x, acc[G][0]);
             acc[G][1] = mfma_bcast<G * 4 + 1>(wt, x[kx].y, acc[G][1]);
@@ -176,13 +177,16 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
     const uint32_t* recs = records + (size_t)bsafe * n_chunks * 16;
     const int n_sub = (K + KC - 1) / KC;
 
-    // weights of entry en: one register per tap, lane l = [g][ci][co]
-    auto load_w = [&](uint32_t en, float (&w)[9]) {
-        const float* wp = wts + (size_t)en * 576 + lane;
+    // Weights: one register per tap, lane l = [g][ci][co].  Fetched an entry ahead (WT = 9), or, with
+    // two pixels per lane, a row of taps ahead (WT = 3): that form needs the registers for the
+    // second pixel's window, and a row already carries 24 multiplies per present group.
+    constexpr int WT = PX == 2 ? 3 : 9;
+    auto load_w = [&](uint32_t en, int ky, float (&w)[WT]) {
+        const float* wp = wts + (size_t)en * 576 + (WT == 3 ? ky * 192 : 0) + lane;
 #pragma unroll
-        for (int t = 0; t < 9; ++t) w[t] = wp[t * 64];
+        for (int t = 0; t < WT; ++t) w[t] = wp[t * 64];
     };
-    float wa[9], wb[9];       // weights of the current and of the next entry of the bundle's list
+    float wa[WT], wb[WT];     // weights in use and weights on their way
     uint32_t dv = 0;          // descriptors of the current 64-channel record, one per lane (lanes 0..15)
     uint32_t q = 0, e = 0;    // position in the record, running entry index
 
@@ -211,13 +215,13 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
                     xr[c] = *(const v4f*)(xl + (xrow[ky] + (s16 ^ g16[j])) + (ky * IWP + c) * 128);
                 }
             };
-            auto row = [&](auto kytag, uint32_t m, const float (&w)[9], const v4f (&xr)[NX]) {
+            auto row = [&](auto kytag, uint32_t m, const float (&w)[WT], const v4f (&xr)[NX]) {
                 constexpr int KY = decltype(kytag)::value;
                 // a taken branch costs the wave tens of cycles: keep "present" the fall-through path
-                if (__builtin_expect((m & 1u) != 0, 1)) row_fma<0, KY, PX, STRIDE, NX>(w, xr, acc);
-                if (__builtin_expect((m & 2u) != 0, 1)) row_fma<1, KY, PX, STRIDE, NX>(w, xr, acc);
-                if (__builtin_expect((m & 4u) != 0, 1)) row_fma<2, KY, PX, STRIDE, NX>(w, xr, acc);
-                if (__builtin_expect((m & 8u) != 0, 1)) row_fma<3, KY, PX, STRIDE, NX>(w, xr, acc);
+                if (__builtin_expect((m & 1u) != 0, 1)) row_fma<0, KY, PX, STRIDE, NX, WT>(w, xr, acc);
+                if (__builtin_expect((m & 2u) != 0, 1)) row_fma<1, KY, PX, STRIDE, NX, WT>(w, xr, acc);
+                if (__builtin_expect((m & 4u) != 0, 1)) row_fma<2, KY, PX, STRIDE, NX, WT>(w, xr, acc);
+                if (__builtin_expect((m & 8u) != 0, 1)) row_fma<3, KY, PX, STRIDE, NX, WT>(w, xr, acc);
             };
             // One entry.  Its weights are in w; the next entry's are fetched into w_nxt meanwhile.
             // Row-ahead (!DEEP): on entry p holds the activations under its first row of taps, on exit
@@ -226,17 +230,31 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
             // next entry's.  Either way consecutive entries swap the two register sets.  A fetch past
             // the sub-chunk's last entry reads the next entry's weights (or the array's slack) and
             // some in-tile activations; they are the next sub-chunk's or unused.
-            auto entry = [&](uint32_t d, uint32_t d_nxt, const float (&w)[9], float (&w_nxt)[9], XW& p, XW& r) {
-                load_w(e + 1, w_nxt);
+            auto entry = [&](uint32_t d, uint32_t d_nxt, float (&w)[WT], float (&w_nxt)[WT], XW& p, XW& r) {
+                if constexpr (WT == 3) {
+                    // weights and activations both run one row ahead; on exit w_nxt and r hold the
+                    // first row of the next entry
+                    load_w(e, 1, w_nxt);
+                    load_x(d, 1, r.r[0]);
+                    row(std::integral_constant<int, 0>{}, d, w, p.r[0]);
+                    load_w(e, 2, w);
+                    load_x(d, 2, p.r[0]);
+                    row(std::integral_constant<int, 1>{}, d, w_nxt, r.r[0]);
+                    load_w(e + 1, 0, w_nxt);
+                    load_x(d_nxt, 0, r.r[0]);
+                    row(std::integral_constant<int, 2>{}, d, w, p.r[0]);
+                    return;
+                }
+                load_w(e + 1, 0, w_nxt);
                 if constexpr (DEEP) {
                     load_x(d_nxt, 0, r.r[0]);
                     load_x(d_nxt, 1, r.r[1]);
                     load_x(d_nxt, 2, r.r[2]);
                     auto group = [&](auto gtag) {
                         constexpr int G = decltype(gtag)::value;
-                        row_fma<G, 0, PX, STRIDE, NX>(w, p.r[0], acc);
-                        row_fma<G, 1, PX, STRIDE, NX>(w, p.r[1], acc);
-                        row_fma<G, 2, PX, STRIDE, NX>(w, p.r[2], acc);
+                        row_fma<G, 0, PX, STRIDE, NX, WT>(w, p.r[0], acc);
+                        row_fma<G, 1, PX, STRIDE, NX, WT>(w, p.r[1], acc);
+                        row_fma<G, 2, PX, STRIDE, NX, WT>(w, p.r[2], acc);
                     };
                     if (__builtin_expect((d & 1u) != 0, 1)) group(std::integral_constant<int, 0>{});
                     if (__builtin_expect((d & 2u) != 0, 1)) group(std::integral_constant<int, 1>{});
@@ -259,21 +277,24 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
                     load_x(d_cur, 1, xa.r[1]);
                     load_x(d_cur, 2, xa.r[2]);
                 }
-                for (;;) {
-                    uint32_t d_nxt = desc(q + 1);
+                // The body is written once and the two register sets are exchanged by name; the
+                // compiler unrolls the loop by two and the exchange costs nothing.  (Unrolling it
+                // by hand, with an exit between the copies, made the accumulators alternate between
+                // two register sets, at eight copies per row and group.)
+                while (mine(d_cur)) {
+                    const uint32_t d_nxt = desc(q + 1);
                     entry(d_cur, d_nxt, wa, wb, xa, xb);
                     ++q, ++e;
                     d_cur = d_nxt;
-                    if (!mine(d_cur)) {              // the fetched weights belong to the next sub-chunk:
 #pragma unroll
-                        for (int t = 0; t < 9; ++t) wa[t] = wb[t];      // keep them where it expects them
-                        break;
+                    for (int t = 0; t < WT; ++t) {
+                        const float tw = wa[t];
+                        wa[t] = wb[t];
+                        wb[t] = tw;
                     }
-                    d_nxt = desc(q + 1);
-                    entry(d_cur, d_nxt, wb, wa, xb, xa);
-                    ++q, ++e;
-                    d_cur = d_nxt;
-                    if (!mine(d_cur)) break;
+                    const XW tx = xa;
+                    xa = xb;
+                    xb = tx;
                 }
             }
         }
@@ -287,7 +308,7 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
 
     issue_x(0);
     e = __builtin_amdgcn_readfirstlane(wo[0]);
-    load_w(e, wa);
+    load_w(e, 0, wa);
     write_x(lds);
     __syncthreads();
     for (int sc = 0; sc < n_sub; sc += 2) {
