@@ -46,6 +46,8 @@ def parse():
                          "whole batch on one stream)")
     ap.add_argument("--graph", action="store_true",
                     help="mobilenet workload: capture the chain in a HIP graph once and time its replays")
+    ap.add_argument("--k3-pattern-share", type=int, default=0, choices=[0, 1, 2, 4],
+                    help="conv3x3: keep 4 of 9 weights inside every kernel first, pattern shared by this many filters")
     ap.add_argument("--dw-pattern", action="store_true",
                     help="mobilenet workload: 3:9 pattern-prune the depthwise layers (groups of 16 channels)")
     return ap.parse_args()
@@ -289,6 +291,9 @@ def run_conv3x3(a, torch, S, W):
     layers, dense, flops, bytes_alg, xs, ys, hws = [], [], [], [], [], [], []
     for idx in range(len(W.RESNET50_3X3)):
         t = W.conv3x3_layer_tensors(5000, idx, B, with_x=False)
+        if a.k3_pattern_share:
+            t["w"] = S.sbn_conv3x3_pattern_apply(t["w"], S.sbn_conv3x3_pattern_select(t["w"], a.k3_pattern_share),
+                                                 a.k3_pattern_share)
         mask = S.sbn_prune_magnitude(t["w"], S.SBN_CONV3X3, a.go, 4, pct)
         p = S.sbn_pack(S.SBN_CONV3X3, t["w"], a.go, 4, mask=mask, bias=t["bias"], act=S.SBN_ACT_RELU, device=0)
         layers.append(p)
@@ -340,7 +345,9 @@ def run_conv3x3(a, torch, S, W):
         "unit": "GFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"4 ResNet-50-shaped 3x3 convs (C 64..512, spatial 56..7), batch {B}, fp32, "
-                               f"kernel-level group sparsity {pct}% (go={a.go} gi=4 whole kernels)", "batch": B,
+                               f"kernel-level group sparsity {pct}% (go={a.go} gi=4 whole kernels)"
+                               + (f", 4-of-9 patterns inside kept kernels shared by {a.k3_pattern_share} filters "
+                                  "(stored zeros are multiplied and counted)" if a.k3_pattern_share else ""), "batch": B,
                    "sparsity_percent": pct},
         "roofline": {"bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_MFMA_F32_TFLOPS, 4),

@@ -132,6 +132,44 @@ int sbn_dw_pattern_select(const float* w, int c, int go, const uint8_t* keep_den
 int sbn_dw_pattern_apply(const float* w, int c, int go, const uint8_t* pattern, float* w_out);
 
 /*
+ * Pattern pruning inside the kept kernels of a 3x3 layer (Section 3.2, Conv3x3;
+ * Section 3.3's closing remarks).  Every 3x3 kernel (one filter x one input
+ * channel) keeps 4 of its 9 weights, the centre among them: C(8,3) = 56
+ * patterns.  `share` adjacent filters (4, 2 or 1, in the order the layer
+ * runs in) use the same pattern for a given input channel.  Whole kernels are
+ * removed by the block mask of sbn_prune_magnitude / sbn_pack as before; the
+ * usual order is select -> apply -> prune -> pack.
+ *
+ * Taps are numbered ky*3 + kx; the centre is tap 4.  Pattern id p in 0..55 is
+ * the p-th 3-element subset {a < b < c} of the other taps (0,1,2,3,5,6,7,8) in
+ * lexicographic order of (a, b, c); the kernel keeps a, b, c and the centre.
+ * SBN_K3_PATTERN_DENSE keeps all nine.
+ *
+ * sbn_conv3x3_pattern_taps: bit t of *tap_mask_out set = tap t is kept.
+ *
+ * sbn_conv3x3_pattern_select: w host OHWI [c_out][3][3][c_in], c_out a multiple
+ * of share.  Writes pattern_out (uint8 [c_out/share][c_in]): for filter group f
+ * and channel c the pattern with the largest kept l1-norm.  Per tap the
+ * magnitudes of the group's filters are summed in filter order (fp64); a
+ * pattern's score is the sum of its three taps in ascending tap order; ties ->
+ * the lowest id.
+ *
+ * sbn_conv3x3_pattern_apply: w_out = W (.) M as a select (removed weights +0.0,
+ * kept ones bit for bit); w_out may equal w.  Ids above SBN_K3_PATTERN_DENSE
+ * are SBN_EINVAL.
+ *
+ * The device kernel runs pattern-pruned layers through the same path as any
+ * other packed 3x3 layer (zeros inside kept blocks are multiplied): see the
+ * design notes for why the matrix pipe cannot skip single taps here.
+ */
+#define SBN_K3_PATTERNS 56
+#define SBN_K3_PATTERN_DENSE 56
+int sbn_conv3x3_pattern_taps(int pattern, uint32_t* tap_mask_out);
+int sbn_conv3x3_pattern_select(const float* w, int c_out, int c_in, int share, uint8_t* pattern_out);
+int sbn_conv3x3_pattern_apply(const float* w, int c_out, int c_in, int share, const uint8_t* pattern,
+                              float* w_out);
+
+/*
  * Whole-network rearrangement for a chain of layers (Section 3.4).
  * layers[l].w / c_in / c_out / go / gi / kind are read (mask, bias, perms are
  * ignored).  parent[l] is the index of the layer whose output feeds layer l,

@@ -14,6 +14,7 @@ Contents, each following the passage it cites:
     oracle in sbn_oracle.c                         (Section 3.1; Algorithm 1 result)
   * 3:9 pattern group pruning of depthwise 3x3 kernels (Section 3.2, DwConv3x3;
     Algorithm 2's PatternInfo)
+  * 4-of-9 pattern pruning inside kept 3x3 kernels (Section 3.2, Conv3x3)
 
 Pinned by tests/test_oracle_*.py against brute force, library routines,
 closed forms and the paper's printed FLOP totals.  Parity unpinned: quality of
@@ -411,4 +412,69 @@ def dw_pattern_apply(w: np.ndarray, ids: Sequence[int], go: int = 16) -> np.ndar
     for (c0, n), pid in zip(dw_pattern_groups(w.shape[0], go), ids):
         m = dw_pattern_mask(int(pid)).astype(bool)
         out[c0:c0 + n][:, ~m] = 0.0
+    return out
+
+
+# ----------------------------------------------------------------------------
+# Section 3.2, Conv3x3: pattern pruning inside the kept kernels.  Every 3x3
+# kernel keeps 4 of its 9 weights, the centre always among them: C(8,3) = 56
+# patterns.  Adjacent filters (4, 2 or 1) use the same pattern for a given
+# input channel (Section 3.3, closing remarks); the pattern kept is the one
+# with the largest l1-norm.  Numbering (a reading; the paper shows the
+# patterns in a figure only): taps are ky*3 + kx, id p is the p-th 3-subset of
+# the eight non-centre taps in lexicographic order.
+# ----------------------------------------------------------------------------
+
+K3_PATTERNS = 56
+K3_PATTERN_DENSE = 56
+
+
+def conv3x3_pattern_mask(pid: int) -> np.ndarray:
+    """uint8 [3][3] keep-mask of 4-of-9 pattern pid; K3_PATTERN_DENSE keeps everything."""
+    if pid == K3_PATTERN_DENSE:
+        return np.ones((3, 3), dtype=np.uint8)
+    assert 0 <= pid < K3_PATTERNS
+    others = [t for t in range(9) if t != 4]
+    subsets = list(itertools.combinations(others, 3))       # lexicographic in (a, b, c)
+    m = np.zeros(9, dtype=np.uint8)
+    m[4] = 1
+    m[list(subsets[pid])] = 1
+    return m.reshape(3, 3)
+
+
+def conv3x3_pattern_select(w: np.ndarray, share: int = 4) -> np.ndarray:
+    """uint8 [c_out/share][c_in] pattern ids for w OHWI [c_out][3][3][c_in]: per group of `share`
+    adjacent filters and per input channel, the pattern keeping the largest summed magnitude
+    (fp64: per tap over the group's filters in order, then over the pattern's three non-centre
+    taps in ascending order; ties -> the lowest id)."""
+    c_out, _, _, c_in = w.shape
+    assert share in (1, 2, 4) and c_out % share == 0
+    masks = [conv3x3_pattern_mask(p).reshape(9) for p in range(K3_PATTERNS)]
+    ids = np.zeros((c_out // share, c_in), dtype=np.uint8)
+    for f in range(c_out // share):
+        for c in range(c_in):
+            s = [0.0] * 9
+            for t in range(9):
+                for i in range(share):
+                    s[t] += abs(float(w[f * share + i, t // 3, t % 3, c]))
+            best, best_id = -1.0, 0
+            for p in range(K3_PATTERNS):
+                tot = 0.0
+                for t in range(9):
+                    if t != 4 and masks[p][t]:
+                        tot += s[t]
+                if tot > best:
+                    best, best_id = tot, p
+            ids[f, c] = best_id
+    return ids
+
+
+def conv3x3_pattern_apply(w: np.ndarray, ids: np.ndarray, share: int = 4) -> np.ndarray:
+    """W (.) M for a 3x3 layer: a select, removed weights become +0.0."""
+    c_out, _, _, c_in = w.shape
+    out = w.copy()
+    for n in range(c_out):
+        for c in range(c_in):
+            m = conv3x3_pattern_mask(int(ids[n // share, c])).astype(bool)
+            out[n, :, :, c][~m] = 0.0
     return out

@@ -58,6 +58,9 @@ SYMBOLS = {
     "sbn_dw_pattern_groups": (C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_int), C.c_void_p]),
     "sbn_dw_pattern_select": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "sbn_dw_pattern_apply": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
+    "sbn_conv3x3_pattern_taps": (C.c_int, [C.c_int, C.POINTER(C.c_uint32)]),
+    "sbn_conv3x3_pattern_select": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "sbn_conv3x3_pattern_apply": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "sbn_rearrange": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int,
                                 C.c_uint64, C.c_int, C.POINTER(C.c_void_p)]),
     "sbn_pack": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_void_p)]),

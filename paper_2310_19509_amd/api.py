@@ -17,12 +17,16 @@ __all__ = [
     "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_chain_free",
     "sbn_copy_bytes", "dw_item", "sparse_item", "avgpool_item", "stem_item", "SBN_ITEM_STEM3X3",
     "SBN_DW_PATTERN_DENSE", "sbn_dw_pattern_groups", "sbn_dw_pattern_select", "sbn_dw_pattern_apply",
+    "SBN_K3_PATTERNS", "SBN_K3_PATTERN_DENSE", "sbn_conv3x3_pattern_taps", "sbn_conv3x3_pattern_select",
+    "sbn_conv3x3_pattern_apply",
 ]
 
 SBN_CONV1X1, SBN_CONV3X3 = 1, 3
 SBN_ACT_NONE, SBN_ACT_RELU = 0, 1
 SBN_ITEM_SPARSE, SBN_ITEM_DW3X3, SBN_ITEM_AVGPOOL, SBN_ITEM_STEM3X3 = 1, 2, 3, 4
 SBN_DW_PATTERN_DENSE = 8
+SBN_K3_PATTERNS = 56
+SBN_K3_PATTERN_DENSE = 56
 
 
 class SbnError(RuntimeError):
@@ -163,6 +167,37 @@ def sbn_dw_pattern_apply(w, pattern, go: int = 16) -> np.ndarray:
         raise ValueError("pattern must have one id per group")
     out = np.empty_like(w)
     _check(_lib.lib().sbn_dw_pattern_apply(w.ctypes.data, c, go, pat.ctypes.data, out.ctypes.data))
+    return out
+
+
+def sbn_conv3x3_pattern_taps(pattern: int) -> int:
+    """9-bit mask of the taps (ky*3 + kx) that 4-of-9 pattern `pattern` keeps."""
+    out = C.c_uint32()
+    _check(_lib.lib().sbn_conv3x3_pattern_taps(int(pattern), C.byref(out)))
+    return out.value
+
+
+def sbn_conv3x3_pattern_select(w, share: int = 4) -> np.ndarray:
+    """w OHWI [c_out][3][3][c_in] in the order the layer runs in -> uint8 [c_out/share][c_in] pattern ids."""
+    w = _f32(w)
+    if w.ndim != 4 or w.shape[1:3] != (3, 3):
+        raise ValueError("w must be [c_out][3][3][c_in]")
+    c_out, c_in = w.shape[0], w.shape[3]
+    out = np.zeros((max(c_out // max(share, 1), 0), c_in), dtype=np.uint8)
+    _check(_lib.lib().sbn_conv3x3_pattern_select(w.ctypes.data, c_out, c_in, share, out.ctypes.data))
+    return out
+
+
+def sbn_conv3x3_pattern_apply(w, pattern, share: int = 4) -> np.ndarray:
+    w = _f32(w)
+    if w.ndim != 4 or w.shape[1:3] != (3, 3):
+        raise ValueError("w must be [c_out][3][3][c_in]")
+    c_out, c_in = w.shape[0], w.shape[3]
+    pat = np.ascontiguousarray(pattern, dtype=np.uint8)
+    if share in (1, 2, 4) and c_out % share == 0 and pat.shape != (c_out // share, c_in):
+        raise ValueError("pattern must be [c_out/share][c_in]")
+    out = np.empty_like(w)
+    _check(_lib.lib().sbn_conv3x3_pattern_apply(w.ctypes.data, c_out, c_in, share, pat.ctypes.data, out.ctypes.data))
     return out
 
 

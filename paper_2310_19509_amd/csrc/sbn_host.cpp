@@ -386,6 +386,90 @@ int sbn_dw_pattern_apply(const float* w, int c, int go, const uint8_t* pattern, 
     return SBN_OK;
 }
 
+// ---- 4-of-9 pattern pruning inside kept 3x3 kernels (Section 3.2, Conv3x3)
+
+// kept taps of a pattern id; the ids enumerate the 3-subsets of the non-centre taps in
+// lexicographic order
+static uint32_t k3_pattern_taps(int pattern)
+{
+    if (pattern == SBN_K3_PATTERN_DENSE) return 0x1FFu;
+    static const int other[8] = {0, 1, 2, 3, 5, 6, 7, 8};
+    int id = 0;
+    for (int a = 0; a < 8; ++a)
+        for (int b = a + 1; b < 8; ++b)
+            for (int c = b + 1; c < 8; ++c, ++id)
+                if (id == pattern) return (1u << other[a]) | (1u << other[b]) | (1u << other[c]) | (1u << 4);
+    return 0;
+}
+
+static int k3_pattern_args(const char* who, int c_out, int c_in, int share)
+{
+    if (share != 1 && share != 2 && share != 4)
+        return fail(SBN_EINVAL, "%s: a pattern is shared by 4, 2 or 1 filters (got %d)", who, share);
+    if (c_out <= 0 || c_in <= 0 || c_out % share)
+        return fail(SBN_ESHAPE, "%s: %d filters do not split into groups of %d", who, c_out, share);
+    return SBN_OK;
+}
+
+int sbn_conv3x3_pattern_taps(int pattern, uint32_t* tap_mask_out)
+{
+    clear_error();
+    if (!tap_mask_out) return fail(SBN_EINVAL, "sbn_conv3x3_pattern_taps: NULL pointer");
+    if (pattern < 0 || pattern > SBN_K3_PATTERN_DENSE)
+        return fail(SBN_EINVAL, "pattern id %d is not in 0..%d", pattern, SBN_K3_PATTERN_DENSE);
+    *tap_mask_out = k3_pattern_taps(pattern);
+    return SBN_OK;
+}
+
+int sbn_conv3x3_pattern_select(const float* w, int c_out, int c_in, int share, uint8_t* pattern_out)
+{
+    clear_error();
+    if (!w || !pattern_out) return fail(SBN_EINVAL, "sbn_conv3x3_pattern_select: NULL pointer");
+    if (int rc = k3_pattern_args("sbn_conv3x3_pattern_select", c_out, c_in, share)) return rc;
+    uint32_t taps[SBN_K3_PATTERNS];
+    for (int p = 0; p < SBN_K3_PATTERNS; ++p) taps[p] = k3_pattern_taps(p);
+    for (int f = 0; f < c_out / share; ++f)
+        for (int c = 0; c < c_in; ++c) {
+            double s[9];
+            for (int t = 0; t < 9; ++t) {
+                s[t] = 0.0;
+                for (int i = 0; i < share; ++i)
+                    s[t] += std::fabs((double)w[((size_t)(f * share + i) * 9 + t) * c_in + c]);
+            }
+            double best = -1.0;
+            int best_id = 0;
+            for (int p = 0; p < SBN_K3_PATTERNS; ++p) {
+                double tot = 0.0;
+                for (int t = 0; t < 9; ++t)
+                    if (t != 4 && ((taps[p] >> t) & 1u)) tot += s[t];
+                if (tot > best) best = tot, best_id = p;
+            }
+            pattern_out[(size_t)f * c_in + c] = (uint8_t)best_id;
+        }
+    return SBN_OK;
+}
+
+int sbn_conv3x3_pattern_apply(const float* w, int c_out, int c_in, int share, const uint8_t* pattern, float* w_out)
+{
+    clear_error();
+    if (!w || !pattern || !w_out) return fail(SBN_EINVAL, "sbn_conv3x3_pattern_apply: NULL pointer");
+    if (int rc = k3_pattern_args("sbn_conv3x3_pattern_apply", c_out, c_in, share)) return rc;
+    const size_t n_ids = (size_t)(c_out / share) * c_in;
+    for (size_t i = 0; i < n_ids; ++i)
+        if (pattern[i] > SBN_K3_PATTERN_DENSE)
+            return fail(SBN_EINVAL, "pattern id %d at position %zu is not in 0..%d", pattern[i], i, SBN_K3_PATTERN_DENSE);
+    uint32_t taps[SBN_K3_PATTERN_DENSE + 1];
+    for (int p = 0; p <= SBN_K3_PATTERN_DENSE; ++p) taps[p] = k3_pattern_taps(p);
+    for (int n = 0; n < c_out; ++n)
+        for (int t = 0; t < 9; ++t)
+            for (int c = 0; c < c_in; ++c) {
+                const size_t i = ((size_t)n * 9 + t) * c_in + c;
+                const uint32_t keep = taps[pattern[(size_t)(n / share) * c_in + c]];
+                w_out[i] = (keep >> t) & 1u ? w[i] : 0.0f;
+            }
+    return SBN_OK;
+}
+
 int sbn_rearrange(const sbn_layer_desc_t* layers, int n_layers, const int* parent, const int* keep_output_order,
                   int pct, uint64_t seed, int max_iters, int32_t* const* perm_out)
 {

@@ -94,6 +94,29 @@ def test_taps_are_not_transposed():
     assert np.array_equal(y, expect)
 
 
+@pytest.mark.parametrize("share,stride", [(4, 1), (2, 1), (1, 2)])
+def test_pattern_pruned_kernels(share, stride):
+    """Section 3.2, Conv3x3: 4 of 9 weights kept inside every kernel (pattern shared by `share`
+    adjacent filters of the order the layer runs in), then whole kernels removed by block magnitude."""
+    K, N = 72, 48
+    w = W.normal_weights(8200 + share, (N, 3, 3, K), (2.0 / (9 * K)) ** 0.5)
+    bias = W.normal_weights(8210 + share, (N,), 0.01)
+    x = W.uniform_activation(8220 + share, (2, 13, 18, K))
+    perm_out = np.random.default_rng(8230 + share).permutation(N).astype(np.int32)
+    wp = R.permute_weights(w, perm_out, None)
+    ids = S.sbn_conv3x3_pattern_select(wp, share)
+    assert ids.tolist() == R.conv3x3_pattern_select(wp, share).tolist()
+    wm_p = S.sbn_conv3x3_pattern_apply(wp, ids, share)
+    assert np.array_equal(wm_p.view(np.uint32), R.conv3x3_pattern_apply(wp, ids, share).view(np.uint32))
+    wm = np.empty_like(wm_p)
+    wm[perm_out] = wm_p                                           # back to the original filter order
+    y, ref, bound = run_layer(x, wm, 4, 4, stride=stride, bias=bias, perm_out=perm_out, act=S.SBN_ACT_RELU, pct=60)
+    assert_within_bound(y, ref, bound, f"pattern share {share}")
+    # the oracle's layer on weights masked by hand: kept kernels carry exactly four weights
+    per_kernel = np.count_nonzero(wm.transpose(0, 3, 1, 2).reshape(N * K, 9), axis=1)
+    assert per_kernel.max() <= 4 and (per_kernel == 4).mean() > 0.99
+
+
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
 def test_resnet50_shapes_batch32_sampled(idx):
     """Config 5: ResNet-50-shaped 3x3 layers at batch 32, 70 % kernel-group sparsity; sampled images."""

@@ -217,3 +217,40 @@ def test_dw_pattern_errors():
         S.sbn_dw_pattern_groups(16, 5)                       # group size
     with pytest.raises(S.SbnError):
         S.sbn_dw_pattern_apply(np.zeros((16, 3, 3), np.float32), np.array([9], np.uint8), 16)
+
+
+# ---- 4-of-9 pattern pruning inside kept 3x3 kernels (Section 3.2, Conv3x3)
+
+def test_conv3x3_pattern_taps_match_the_oracle():
+    for pid in list(range(S.SBN_K3_PATTERNS)) + [S.SBN_K3_PATTERN_DENSE]:
+        want = sum(1 << t for t in range(9) if R.conv3x3_pattern_mask(pid).reshape(9)[t])
+        assert S.sbn_conv3x3_pattern_taps(pid) == want
+    assert S.SBN_K3_PATTERNS == R.K3_PATTERNS and S.SBN_K3_PATTERN_DENSE == R.K3_PATTERN_DENSE
+
+
+@pytest.mark.parametrize("c_out,c_in,share,seed", [(8, 8, 4, 1), (8, 12, 2, 2), (12, 5, 1, 3), (16, 7, 4, 4)])
+def test_conv3x3_pattern_select_and_apply_bit_exact(c_out, c_in, share, seed):
+    w = W.normal_weights(7800 + seed, (c_out, 3, 3, c_in), 0.3)
+    w[0, 1, 1, 0] = -0.0
+    w[1, 0, 0, 1] = -0.0
+    want = R.conv3x3_pattern_select(w, share)
+    got = S.sbn_conv3x3_pattern_select(w, share)
+    assert got.shape == want.shape and got.tolist() == want.tolist()
+    got[0, 0] = S.SBN_K3_PATTERN_DENSE                   # a group left dense
+    wm = S.sbn_conv3x3_pattern_apply(w, got, share)
+    assert np.array_equal(wm.view(np.uint32), R.conv3x3_pattern_apply(w, got, share).view(np.uint32))
+    kept = np.count_nonzero(wm.view(np.uint32) & 0x7FFFFFFF)
+    assert kept <= 4 * c_out * c_in + 5 * share
+
+
+def test_conv3x3_pattern_ties_and_errors():
+    w = np.ones((4, 3, 3, 3), dtype=np.float32)
+    assert S.sbn_conv3x3_pattern_select(w, 4).tolist() == [[0, 0, 0]] == R.conv3x3_pattern_select(w, 4).tolist()
+    with pytest.raises(S.SbnError):
+        S.sbn_conv3x3_pattern_select(w, 3)                   # share must be 4, 2 or 1
+    with pytest.raises(S.SbnError):
+        S.sbn_conv3x3_pattern_select(np.ones((6, 3, 3, 3), np.float32), 4)   # 6 filters, groups of 4
+    with pytest.raises(S.SbnError):
+        S.sbn_conv3x3_pattern_apply(w, np.full((1, 3), 57, np.uint8), 4)
+    with pytest.raises(S.SbnError):
+        S.sbn_conv3x3_pattern_taps(57)
