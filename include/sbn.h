@@ -253,6 +253,21 @@ int sbn_conv3x3_sparse(const sbn_packed_t* p, const float* x, float* y,
                        int n, int h, int w, void* stream);
 
 /*
+ * Testing and benchmarking hook: both run calls pick, per launch, one of
+ * several forms of their kernel from the shape (tile size, channels staged at
+ * a time, input channels split over waves).  This call forces one form for all
+ * later launches of that kind in the process (0 = back to automatic), so that
+ * every form can be checked on every shape; results never depend on the form
+ * beyond summation order.  kind: SBN_CONV1X1 (forms 11, 12, 14, 21, 22: pixels
+ * per lane and accumulator sets; 504, 508, 516: 4, 8, 16 waves splitting the
+ * input channels) or SBN_CONV3X3 (1, 2, 3: one pixel per lane, two pixels per
+ * lane, entry-ahead fetch).  Layers whose shape leaves no choice (c_in <= 64,
+ * c_in not a multiple of 4, stride 2) ignore it.  Unknown values: SBN_EINVAL.
+ * Not synchronised with launches in flight on other threads.
+ */
+int sbn_force_kernel_form(int kind, int form);
+
+/*
  * A stack of layers run back to back on one stream (Section 3.4: activations
  * stay in rearranged channel order between layers; Section 3.5 engine).
  */

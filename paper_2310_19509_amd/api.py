@@ -17,7 +17,7 @@ __all__ = [
     "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_chain_free",
     "sbn_copy_bytes", "dw_item", "sparse_item", "avgpool_item", "stem_item", "SBN_ITEM_STEM3X3",
     "SBN_DW_PATTERN_DENSE", "sbn_dw_pattern_groups", "sbn_dw_pattern_select", "sbn_dw_pattern_apply",
-    "SBN_K3_PATTERNS", "SBN_K3_PATTERN_DENSE", "sbn_conv3x3_pattern_taps", "sbn_conv3x3_pattern_select",
+    "sbn_force_kernel_form", "SBN_K3_PATTERNS", "SBN_K3_PATTERN_DENSE", "sbn_conv3x3_pattern_taps", "sbn_conv3x3_pattern_select",
     "sbn_conv3x3_pattern_apply",
 ]
 
@@ -168,6 +168,11 @@ def sbn_dw_pattern_apply(w, pattern, go: int = 16) -> np.ndarray:
     out = np.empty_like(w)
     _check(_lib.lib().sbn_dw_pattern_apply(w.ctypes.data, c, go, pat.ctypes.data, out.ctypes.data))
     return out
+
+
+def sbn_force_kernel_form(kind: int, form: int) -> None:
+    """Force one form of the 1x1 or 3x3 kernel for all later launches (0 = automatic); for tests."""
+    _check(_lib.lib().sbn_force_kernel_form(int(kind), int(form)))
 
 
 def sbn_conv3x3_pattern_taps(pattern: int) -> int:

@@ -458,8 +458,7 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
 {
     hipStream_t st = (hipStream_t)stream;
     const int K = p->c_in;
-    const char* forced = getenv("SBN_K1_VARIANT");      // testing / benchmarking override, read per launch
-    const int force = forced ? atoi(forced) : 0;
+    const int force = forced_kernel_form(SBN_CONV1X1);  // testing / benchmarking override
     if (K % 4) {
         if (K <= 32) return launch<1, 2, 32, false, false>(p, x, y, M, st);
         if (K <= 64) return launch<1, 2, 64, false, false>(p, x, y, M, st);

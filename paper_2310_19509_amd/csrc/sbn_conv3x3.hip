@@ -18,7 +18,8 @@
 //
 // Per entry (a 4-channel piece kept by at least one group of the bundle) the
 // wave holds the entry's 9 x 64 weights ([tap][group][ci][co], one register
-// per tap, fetched one entry ahead) and walks the three rows of taps: the
+// per tap, fetched one entry ahead; with PX = 2 one row of taps at a time,
+// fetched a row ahead) and walks the three rows of taps: the
 // lane reads the row's shifted 16-byte activation vectors (one row ahead of
 // the arithmetic) and, for every present group, issues 12 v_mfma_f32_4x4x1
 // per pixel: the weight column [co 0..3] of (group, ci) is broadcast from
@@ -28,7 +29,6 @@
 // with v_readlane.
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
 #include <type_traits>
 
 #include "sbn_internal.h"
@@ -381,8 +381,7 @@ int launch_conv3x3(const sbn_packed* p, const float* x, float* y, int n, int h, 
     if (p->stride == 2) return launch<2, 1, false>(p, x, y, n, h, w, st);
     // Variant: two pixels per lane unless the 16-wide tiles would be mostly empty or would leave
     // the chip short of waves; with at most about two waves per SIMD the entry-ahead variant.
-    const char* forced = getenv("SBN_K3_VARIANT");      // testing / benchmarking override, read per launch
-    int variant = forced ? atoi(forced) : 0;
+    int variant = forced_kernel_form(SBN_CONV3X3);      // testing / benchmarking override
     if (!variant) {
         const long long col_tiles = (p->dev.n_bundles + 3) / 4;
         const long long wg1 = (long long)n * ((w + 7) / 8) * ((h + 7) / 8) * col_tiles;

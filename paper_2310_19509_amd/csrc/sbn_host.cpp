@@ -2,6 +2,7 @@
 // rearrangement and the canonical group-sparse packer (offline steps of the
 // method: Section 3.2, Section 3.4, and the "sparse info" of Algorithm 1).
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -26,6 +27,10 @@ int fail(int code, const char* fmt, ...)
 }
 
 void clear_error() { g_err.clear(); }
+
+// kernel form forced by sbn_force_kernel_form, per layer kind; 0 = chosen per launch
+static std::atomic<int> g_form1x1{0}, g_form3x3{0};
+int forced_kernel_form(int kind) { return (kind == SBN_CONV3X3 ? g_form3x3 : g_form1x1).load(std::memory_order_relaxed); }
 
 bool is_permutation(const int32_t* p, int n)
 {
@@ -272,6 +277,22 @@ using namespace sbn;
 extern "C" {
 
 const char* sbn_last_error(void) { return sbn::g_err.c_str(); }
+
+int sbn_force_kernel_form(int kind, int form)
+{
+    clear_error();
+    static const int forms1x1[] = {0, 11, 12, 14, 21, 22, 504, 508, 516}, forms3x3[] = {0, 1, 2, 3};
+    bool ok = false;
+    if (kind == SBN_CONV1X1)
+        for (int f : forms1x1) ok |= f == form;
+    else if (kind == SBN_CONV3X3)
+        for (int f : forms3x3) ok |= f == form;
+    else
+        return fail(SBN_EINVAL, "sbn_force_kernel_form: kind must be SBN_CONV1X1 or SBN_CONV3X3 (got %d)", kind);
+    if (!ok) return fail(SBN_EINVAL, "sbn_force_kernel_form: %d is not a kernel form of this kind", form);
+    (kind == SBN_CONV3X3 ? sbn::g_form3x3 : sbn::g_form1x1).store(form, std::memory_order_relaxed);
+    return SBN_OK;
+}
 
 int sbn_prune_magnitude(const float* w, int kind, int c_in, int c_out, int go, int gi, int pct, uint8_t* mask_out)
 {

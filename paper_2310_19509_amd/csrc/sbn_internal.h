@@ -16,6 +16,7 @@ namespace sbn {
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();
 int dw_group_starts(int c, int go, std::vector<int>& start);   // pattern groups of a depthwise layer (+ c at the end)
+int forced_kernel_form(int kind);                              // sbn_force_kernel_form's value, 0 = automatic
 
 // ---- device-side layout ----------------------------------------------------
 // The canonical rows (one per output group of `go` filters) are regrouped for

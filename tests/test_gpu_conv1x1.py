@@ -73,16 +73,19 @@ def test_shapes(n, h, w, K, N, go, gi, pct, use_bias, relu, perms):
 @pytest.mark.parametrize("variant", [11, 12, 14, 21, 22, 504, 508, 516])
 @pytest.mark.parametrize("n,h,w,K,N,pct", [(3, 9, 11, 128, 256, 30), (1, 7, 7, 512, 1024, 70), (2, 13, 5, 72, 40, 50),
                                              (1, 20, 20, 320, 64, 0)])
-def test_every_multi_chunk_kernel_form(monkeypatch, variant, n, h, w, K, N, pct):
+def test_every_multi_chunk_kernel_form(variant, n, h, w, K, N, pct):
     """Layers with more than 64 input channels have several kernel forms (pixel sets per wave,
-    partial sums per group, 64- or 32-channel chunks) chosen by launch size; each is forced in turn
-    (the library reads the variable at every launch) and must match the oracle on the same input."""
-    monkeypatch.setenv("SBN_K1_VARIANT", str(variant))
+    partial sums per group, 64- or 32-channel chunks, input channels split over waves) chosen by
+    launch size; each is forced in turn and must match the oracle on the same input."""
     seed = 7500 + K + N + pct
     wt = W.he_weights(seed, N, 1, 1, K)
     b = W.small_bias(seed + 1, N) * 20
     x = W.uniform_activation(seed + 2, (n, h, w, K))
-    y, ref, bound = run_layer(x, wt, 4, 4, bias=b, act=S.SBN_ACT_RELU, pct=pct)
+    S.sbn_force_kernel_form(S.SBN_CONV1X1, variant)
+    try:
+        y, ref, bound = run_layer(x, wt, 4, 4, bias=b, act=S.SBN_ACT_RELU, pct=pct)
+    finally:
+        S.sbn_force_kernel_form(S.SBN_CONV1X1, 0)
     assert_within_bound(y, ref, bound, f"variant {variant} case {n,h,w,K,N,pct}")
 
 

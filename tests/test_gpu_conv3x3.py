@@ -51,16 +51,11 @@ CASES = [
 
 
 @pytest.fixture
-def kernel_variant(monkeypatch):
-    """Forces one form of the stride-1 kernel (the library reads the variable at every launch):
+def kernel_variant():
+    """Forces one form of the stride-1 kernel for the launches of the test:
     1 = one pixel per lane, row-ahead; 2 = two pixels per lane; 3 = one pixel per lane, entry-ahead."""
-    def force(v):
-        if v:
-            monkeypatch.setenv("SBN_K3_VARIANT", str(v))
-        else:
-            monkeypatch.delenv("SBN_K3_VARIANT", raising=False)
-    yield force
-    monkeypatch.delenv("SBN_K3_VARIANT", raising=False)
+    yield lambda v: S.sbn_force_kernel_form(S.SBN_CONV3X3, v)
+    S.sbn_force_kernel_form(S.SBN_CONV3X3, 0)
 
 
 @pytest.mark.parametrize("variant", [0, 1, 2, 3])

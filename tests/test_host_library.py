@@ -254,3 +254,13 @@ def test_conv3x3_pattern_ties_and_errors():
         S.sbn_conv3x3_pattern_apply(w, np.full((1, 3), 57, np.uint8), 4)
     with pytest.raises(S.SbnError):
         S.sbn_conv3x3_pattern_taps(57)
+
+
+def test_force_kernel_form_validates_its_arguments():
+    S.sbn_force_kernel_form(S.SBN_CONV1X1, 21)
+    S.sbn_force_kernel_form(S.SBN_CONV1X1, 0)
+    S.sbn_force_kernel_form(S.SBN_CONV3X3, 2)
+    S.sbn_force_kernel_form(S.SBN_CONV3X3, 0)
+    for kind, form in [(S.SBN_CONV1X1, 13), (S.SBN_CONV3X3, 4), (S.SBN_CONV3X3, -1), (99, 0)]:
+        with pytest.raises(S.SbnError):
+            S.sbn_force_kernel_form(kind, form)
