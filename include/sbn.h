@@ -261,7 +261,8 @@ int sbn_conv3x3_sparse(const sbn_packed_t* p, const float* x, float* y,
  * beyond summation order.  kind: SBN_CONV1X1 (forms 11, 12, 14, 21, 22: pixels
  * per lane and accumulator sets; 504, 508, 516: 4, 8, 16 waves splitting the
  * input channels) or SBN_CONV3X3 (1, 2, 3: one pixel per lane, two pixels per
- * lane, entry-ahead fetch).  Layers whose shape leaves no choice (c_in <= 64,
+ * lane, entry-ahead fetch; 32: entry-ahead with the input channels split over
+ * two halves of an eight-wave workgroup).  Layers whose shape leaves no choice (c_in <= 64,
  * c_in not a multiple of 4, stride 2) ignore it.  Unknown values: SBN_EINVAL.
  * Not synchronised with launches in flight on other threads.
  */

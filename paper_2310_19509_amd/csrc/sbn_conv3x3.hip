@@ -25,8 +25,12 @@
 // per pixel: the weight column [co 0..3] of (group, ci) is broadcast from
 // lanes 4*abid..4*abid+3 to all 16 blocks and meets the activations of pixels
 // 4b..4b+3, so accumulator register i of lane L is output channel i of pixel
-// L.  Descriptors of a 64-channel record are held one per lane and broadcast
-// with v_readlane.
+// L.  The (up to 8) descriptors of a sub-chunk's record are held one per lane
+// and broadcast with v_readlane.
+//
+// Launches too small to give every SIMD several waves use a workgroup of
+// eight waves instead: two slices of four, each multiplying every second
+// sub-chunk out of its own buffers, partial sums added through LDS at the end.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -50,7 +54,9 @@ __device__ __forceinline__ v4f mfma_bcast(float w, float x, v4f c)
 // One row of taps (ky = KY, kx = 0..2) of group G over the lane's PX pixels.  w holds the entry's
 // nine taps (WT = 9) or just this row's three (WT = 3), lane l = [g][ci][co]; x holds the
 // (PX-1)*STRIDE+3 input columns under the pixels.
-// PX = 1: acc[G][0/1] are two partial sums of the one pixel; PX = 2: acc[G][p] is pixel p.
+// PX = 1: acc[G][0/1] are two partial sums of the one pixel (a dependent MFMA issues later than an
+// independent one, which shows when a SIMD holds one or two waves: a single sum was measured 8-20 %
+// slower there); PX = 2: acc[G][p] is pixel p.
 template <int G, int KY, int PX, int STRIDE, int NX, int WT>
 __device__ __forceinline__ void row_fma(const float (&w)[WT], const v4f (&x)[NX], v4f (&acc)[4][2])
 {
@@ -76,13 +82,13 @@ __device__ __forceinline__ void row_fma(const float (&w)[WT], const v4f (&x)[NX]
     }
 }
 
-template <int STRIDE, int PX, bool DEEP>
-__global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ x, float* __restrict__ y,
+template <int STRIDE, int PX, bool DEEP, int SPLIT>
+__global__ __launch_bounds__(256 * SPLIT) void conv3x3_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                       const uint32_t* __restrict__ records,
                                                       const uint32_t* __restrict__ woff,
                                                       const float* __restrict__ wts, const float* __restrict__ bias,
                                                       int H, int W, int OH, int OW,
-                                                      int K, int N, int n_bundles, int n_chunks, int n_col_tiles,
+                                                      int K, int N, int n_bundles, int n_sub, int n_col_tiles,
                                                       int tiles_x, int tiles_y, int n_pix_tiles, int act)
 {
     constexpr int TW = 8 * PX;                         // output tile width
@@ -104,12 +110,23 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
     struct XW {
         v4f r[DEEP ? 3 : 1][NX];
     };
-    constexpr int OBUF = 64 * OS;
-    __shared__ __attribute__((aligned(16))) float lds[XBUF > OBUF ? XBUF : OBUF];
-    __shared__ __attribute__((aligned(16))) float lds_b[DB ? XBUF : 4];
+    // SPLIT > 1: the workgroup has SPLIT slices of four waves; slice s multiplies the sub-chunks
+    // s, s + SPLIT, ... out of its own pair of buffers and the partial sums are added through LDS
+    // at the end.  For launches of at most one workgroup per CU, where the waves of a plain
+    // workgroup would have a SIMD each to themselves and nothing to hide their waits behind.
+    static_assert(SPLIT == 1 || (PX == 1 && STRIDE == 1), "the input channels are split for the one-pixel stride-1 form only");
+    constexpr int OBUF = 64 * OS;                      // epilogue: 64 pixels x 64 channels
+    constexpr int RBUF = (SPLIT - 1) * 4 * 64 * 16;    // partial sums of the slices above 0
+    constexpr int NBUF = DB ? 2 : 1;
+    constexpr int LDSF = SPLIT * NBUF * XBUF > OBUF + RBUF ? SPLIT * NBUF * XBUF : OBUF + RBUF;
+    __shared__ __attribute__((aligned(16))) float lds_all[LDSF];
 
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tid = SPLIT == 1 ? threadIdx.x : threadIdx.x & 255;                     // thread within the slice
+    const int slice = SPLIT == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) & 3;
+    float* const lds = lds_all + slice * NBUF * XBUF;
+    float* const lds_b = DB ? lds + XBUF : lds;
 
     // workgroup -> (pixel tile, column tile): column tiles of one pixel tile run on one XCD
     const int id = blockIdx.x;
@@ -133,12 +150,12 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
     //      thread keeps its column and walks pixels t/8, t/8 + 32, ...  Positions outside the
     //      image load some inside position and are replaced by zeros on the way to LDS.
     const float* xi = x + img * H * W * K;
-    const int col4 = (threadIdx.x & 7) * 4;
+    const int col4 = (tid & 7) * 4;
     int goff[NL];                 // element offset of the slot's (clamped) input pixel in the image
     uint32_t inside = 0;          // bit i: slot i is a real position
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-        int pix = i * 32 + (threadIdx.x >> 3);
+        int pix = i * 32 + (tid >> 3);
         pix = pix < NPIX ? pix : NPIX - 1;
         const int iy = iy0 + pix / IW, ix = ix0 + pix % IW;
         if (iy >= 0 && iy < H && ix >= 0 && ix < W) inside |= 1u << i;
@@ -153,7 +170,7 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
     auto write_x = [&](float* buf) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int pix = i * 32 + (threadIdx.x >> 3);
+            const int pix = i * 32 + (tid >> 3);
             const v4f v = (inside >> i) & 1u ? stage_reg[i] : (v4f){0.f, 0.f, 0.f, 0.f};
             const int r = pix / IW, c = pix % IW;
             const int g = PX == 1 && STRIDE == 1 ? c & 7 : (c >> 1) & 7;
@@ -173,9 +190,9 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
 #pragma unroll
     for (int j = 0; j < NG; ++j) g16[j] = ((PX == 1 && STRIDE == 1 ? col0 + j : (col0 >> 1) + j) & 7) << 4;
 
-    const uint32_t* wo = woff + (size_t)bsafe * (n_chunks + 1);
-    const uint32_t* recs = records + (size_t)bsafe * n_chunks * 16;
-    const int n_sub = (K + KC - 1) / KC;
+    // the bundle's tables: one record of 8 descriptors and one first-entry index per 32 channels
+    const uint32_t* wo = woff + (size_t)bsafe * (n_sub + 1);
+    const uint32_t* recs = records + (size_t)bsafe * n_sub * 8;
 
     // Weights: one register per tap, lane l = [g][ci][co].  Fetched an entry ahead (WT = 9), or, with
     // two pixels per lane, a row of taps ahead (WT = 3): that form needs the registers for the
@@ -187,25 +204,36 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
         for (int t = 0; t < WT; ++t) w[t] = wp[t * 64];
     };
     float wa[WT], wb[WT];     // weights in use and weights on their way
-    uint32_t dv = 0;          // descriptors of the current 64-channel record, one per lane (lanes 0..15)
-    uint32_t q = 0, e = 0;    // position in the record, running entry index
+    float wn[SPLIT > 1 ? WT : 1];   // SPLIT > 1: first weights of the slice's next sub-chunk
+    // dv: descriptors of the sub-chunk being multiplied, one per lane (lanes 0..7); e: the entry
+    // whose first weights are in wa.  A bundle's entries are numbered in channel order, so with
+    // SPLIT = 1 the entry after a sub-chunk's last is the next sub-chunk's first and e just counts
+    // on.  With SPLIT > 1 the first weights of the slice's next sub-chunk (entry e1, read from the
+    // table a round earlier) are fetched separately while this one is multiplied.
+    uint32_t dv = 0, e = 0, e1 = 0;
+    auto clamp_sc = [&](int sc) { return sc < n_sub ? sc : n_sub - 1; };
 
-    // One sub-chunk of 32 channels: fetch the next one, multiply this one, publish the next.
+    // One sub-chunk of 32 channels: fetch the slice's next one, multiply this one, publish the next.
     auto sub_chunk = [&](int sc, const float* xbuf, float* xnext) {
-        if (DB) issue_x(sc + 1 < n_sub ? sc + 1 : sc);      // unconditional: loads under a branch
-                                                            // would be waited for before the arithmetic
-        const uint32_t h = sc & 1;
-        if (h == 0) {                                       // a new 64-channel record
-            dv = recs[(sc >> 1) * 16 + (lane & 15)];
-            q = 0;
+        const int sc_nxt = clamp_sc(sc + SPLIT);
+        uint32_t dv_nxt = 0;
+        if (DB) {                                           // unconditional: loads under a branch
+            issue_x(sc_nxt);                                // would be waited for before the arithmetic
+            dv_nxt = recs[sc_nxt * 8 + (lane & 7)];
+        }
+        uint32_t e2 = 0;
+        if constexpr (SPLIT > 1) {
+            e2 = wo[clamp_sc(sc + 2 * SPLIT)];
+            load_w(e1, 0, wn);
         }
 
-        if (active) {
+        if (active && sc < n_sub) {
             const char* xl = (const char*)xbuf;
+            uint32_t q = 0;                                 // position in the record
             auto desc = [&](uint32_t qq) -> uint32_t {
-                return qq < 16 ? (uint32_t)__builtin_amdgcn_readlane((int)dv, (int)qq) : 0u;
+                return qq < 8 ? (uint32_t)__builtin_amdgcn_readlane((int)dv, (int)qq) : 0u;
             };
-            auto mine = [&](uint32_t d) { return d != 0 && ((d >> 15) & 1u) == h; };
+            auto mine = [&](uint32_t d) { return d != 0; };
             // activations under one row of taps of the piece named by descriptor d
             auto load_x = [&](uint32_t d, int ky, v4f (&xr)[NX]) {
                 const int s16 = (int)((d >> 8) & 0x70u);     // 16 * (piece within the 32-channel sub-chunk)
@@ -228,9 +256,11 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
             // r holds those of the next entry's first row.  Entry-ahead (DEEP, for launches with so
             // few waves per SIMD that latency counts): p holds the whole window and r receives the
             // next entry's.  Either way consecutive entries swap the two register sets.  A fetch past
-            // the sub-chunk's last entry reads the next entry's weights (or the array's slack) and
-            // some in-tile activations; they are the next sub-chunk's or unused.
+            // the sub-chunk's last entry reads some in-tile activations that are not used, and the
+            // weights of the first entry of the slice's next sub-chunk (past the last sub-chunk:
+            // of some entry, or the array's slack).
             auto entry = [&](uint32_t d, uint32_t d_nxt, float (&w)[WT], float (&w_nxt)[WT], XW& p, XW& r) {
+                const uint32_t e_fetch = e + 1;     // SPLIT > 1: not used after the sub-chunk's last entry
                 if constexpr (WT == 3) {
                     // weights and activations both run one row ahead; on exit w_nxt and r hold the
                     // first row of the next entry
@@ -240,12 +270,12 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
                     load_w(e, 2, w);
                     load_x(d, 2, p.r[0]);
                     row(std::integral_constant<int, 1>{}, d, w_nxt, r.r[0]);
-                    load_w(e + 1, 0, w_nxt);
+                    load_w(e_fetch, 0, w_nxt);
                     load_x(d_nxt, 0, r.r[0]);
                     row(std::integral_constant<int, 2>{}, d, w, p.r[0]);
                     return;
                 }
-                load_w(e + 1, 0, w_nxt);
+                load_w(e_fetch, 0, w_nxt);
                 if constexpr (DEEP) {
                     load_x(d_nxt, 0, r.r[0]);
                     load_x(d_nxt, 1, r.r[1]);
@@ -298,22 +328,57 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
                 }
             }
         }
+        if constexpr (SPLIT > 1) {
+#pragma unroll
+            for (int t = 0; t < WT; ++t) wa[t] = wn[t];
+            e = e1;
+            e1 = __builtin_amdgcn_readfirstlane(e2);
+        }
         if (!DB) {                       // single buffer: fetch after everyone has finished reading it
             __syncthreads();
-            issue_x(sc + 1 < n_sub ? sc + 1 : sc);
+            issue_x(sc_nxt);
+            dv_nxt = recs[sc_nxt * 8 + (lane & 7)];
         }
         write_x(xnext);
+        dv = dv_nxt;
         __syncthreads();
     };
 
-    issue_x(0);
-    e = __builtin_amdgcn_readfirstlane(wo[0]);
-    load_w(e, 0, wa);
-    write_x(lds);
-    __syncthreads();
-    for (int sc = 0; sc < n_sub; sc += 2) {
-        sub_chunk(sc, lds, DB ? lds_b : lds);
-        if (sc + 1 < n_sub) sub_chunk(sc + 1, DB ? lds_b : lds, lds);
+    {
+        const int sc0 = clamp_sc(slice), sc1 = clamp_sc(slice + SPLIT);
+        issue_x(sc0);
+        dv = recs[sc0 * 8 + (lane & 7)];
+        e = __builtin_amdgcn_readfirstlane(wo[sc0]);
+        e1 = __builtin_amdgcn_readfirstlane(wo[sc1]);
+        load_w(e, 0, wa);
+        write_x(lds);
+        __syncthreads();
+    }
+    // every slice runs the same number of rounds (and barriers); a slice whose turn lies past the
+    // last sub-chunk stages the last one again and multiplies nothing
+    const int n_rounds = (n_sub + SPLIT - 1) / SPLIT;
+    for (int i = 0; i < n_rounds; i += 2) {
+        sub_chunk(slice + i * SPLIT, lds, lds_b);
+        if (i + 1 < n_rounds) sub_chunk(slice + (i + 1) * SPLIT, lds_b, lds);
+    }
+
+    // ---- SPLIT > 1: add the slices' partial sums into slice 0.  The staging buffers are dead after
+    //      the last barrier above; [0, OBUF) is the epilogue's transpose area, the sums go behind it.
+    if constexpr (SPLIT > 1) {
+        float* red = lds_all + OBUF;
+        if (slice > 0 && active) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *(v4f*)(red + ((((slice - 1) * 4 + wave) * 4 + g) * 64 + lane) * 4) = acc[g][0] + acc[g][1];
+        }
+        __syncthreads();
+        if (slice == 0 && active) {
+#pragma unroll
+            for (int sl = 1; sl < SPLIT; ++sl)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    acc[g][0] += *(const v4f*)(red + ((((sl - 1) * 4 + wave) * 4 + g) * 64 + lane) * 4);
+        }
     }
 
     // ---- epilogue: bias, activation, transpose through LDS, full 256-byte rows per pixel;
@@ -323,7 +388,7 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
 #pragma unroll
     for (int p = 0; p < PX; ++p) {
         if (p) __syncthreads();
-        if (active) {
+        if (active && slice == 0) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 v4f o = (PX == 1 ? acc[g][0] + acc[g][1] : acc[g][p]) + *(const v4f*)(bias + bundle * 16 + g * 4);
@@ -333,22 +398,22 @@ __global__ __launch_bounds__(256) void conv3x3_kernel(const float* __restrict__ 
                     o.z = fmaxf(o.z, 0.f);
                     o.w = fmaxf(o.w, 0.f);
                 }
-                *(v4f*)(lds + lane * OS + wave * 16 + g * 4) = o;
+                *(v4f*)(lds_all + lane * OS + wave * 16 + g * 4) = o;
             }
         }
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int slot = i * 256 + threadIdx.x;
+        for (int i = 0; i < 4 / SPLIT; ++i) {
+            const int slot = i * 256 * SPLIT + threadIdx.x;
             const int pl = slot >> 4, col = (slot & 15) * 4;             // pl: the lane that owned the pixel
             const int oy = oy0 + pl / 8, ox = ox0 + (pl % 8) * PX + p;
             if (oy < OH && ox < OW && ch_base + col < N)
-                *(v4f*)(yi + ((long long)oy * OW + ox) * N + ch_base + col) = *(const v4f*)(lds + pl * OS + col);
+                *(v4f*)(yi + ((long long)oy * OW + ox) * N + ch_base + col) = *(const v4f*)(lds_all + pl * OS + col);
         }
     }
 }
 
-template <int STRIDE, int PX, bool DEEP>
+template <int STRIDE, int PX, bool DEEP, int SPLIT = 1>
 int launch(const sbn_packed* p, const float* x, float* y, int n, int h, int w, hipStream_t st)
 {
     const sbn::DeviceLayout& L = p->dev;
@@ -361,8 +426,8 @@ int launch(const sbn_packed* p, const float* x, float* y, int n, int h, int w, h
         return sbn::fail(SBN_EINVAL, "one image of %d x %d x %d elements is too large for 32-bit offsets", h, w, p->c_in);
     if (grid > 0x7FFFFFFFll || n_pix_tiles > 0x7FFFFFFFll)
         return sbn::fail(SBN_EINVAL, "too many output tiles for one launch (%lld)", n_pix_tiles);
-    hipLaunchKernelGGL((conv3x3_kernel<STRIDE, PX, DEEP>), dim3((unsigned)grid), dim3(256), 0, st, x, y, L.d_records, L.d_woff,
-                       L.d_wts, L.d_bias, h, w, oh, ow, p->c_in, p->c_out, L.n_bundles, L.n_chunks,
+    hipLaunchKernelGGL((conv3x3_kernel<STRIDE, PX, DEEP, SPLIT>), dim3((unsigned)grid), dim3(256 * SPLIT), 0, st, x, y,
+                       L.d_records32, L.d_woff32, L.d_wts, L.d_bias, h, w, oh, ow, p->c_in, p->c_out, L.n_bundles, L.n_chunks32,
                        n_col_tiles, tiles_x, tiles_y, (int)n_pix_tiles, p->act);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return sbn::fail(SBN_EHIP, "conv3x3 launch: %s", hipGetErrorString(e));
@@ -379,18 +444,22 @@ int launch_conv3x3(const sbn_packed* p, const float* x, float* y, int n, int h, 
         return fail(SBN_ESHAPE, "3x3 layers need c_in to be a multiple of 4 on the device (got %d)", p->c_in);
     hipStream_t st = (hipStream_t)stream;
     if (p->stride == 2) return launch<2, 1, false>(p, x, y, n, h, w, st);
-    // Variant: two pixels per lane unless the 16-wide tiles would be mostly empty or would leave
-    // the chip short of waves; with at most about two waves per SIMD the entry-ahead variant.
-    int variant = forced_kernel_form(SBN_CONV3X3);      // testing / benchmarking override
-    if (!variant) {
+    // Form, from timings of ResNet-50-shaped layers at batches 4..128 on a 256-CU part: up to one
+    // plain workgroup per CU the waves would sit alone on their SIMDs, so the input channels are
+    // split over two slices (entry-ahead fetch); up to two per CU the entry-ahead form; above that
+    // two pixels per lane when 16-wide tiles waste no more lanes than 8-wide ones (they need 7 %
+    // less time per pixel), else one pixel per lane, row-ahead (four workgroups per CU).
+    int form = forced_kernel_form(SBN_CONV3X3);         // testing / benchmarking override
+    if (!form) {
         const long long col_tiles = (p->dev.n_bundles + 3) / 4;
-        const long long wg1 = (long long)n * ((w + 7) / 8) * ((h + 7) / 8) * col_tiles;
-        const long long wg2 = (long long)n * ((w + 15) / 16) * ((h + 7) / 8) * col_tiles;
-        variant = w > 8 && wg2 >= 2 * 256 ? 2 : wg1 <= 2 * 256 ? 3 : 1;
+        const long long tiles1 = (long long)((w + 7) / 8) * ((h + 7) / 8), tiles2 = (long long)((w + 15) / 16) * ((h + 7) / 8);
+        const long long wg1 = n * tiles1 * col_tiles;
+        form = wg1 <= 256 ? 32 : wg1 <= 512 ? 3 : w > 8 && tiles2 * 2 * 93 < tiles1 * 100 ? 2 : 1;
     }
-    switch (variant) {
+    switch (form) {
     case 2: return launch<1, 2, false>(p, x, y, n, h, w, st);
     case 3: return launch<1, 1, true>(p, x, y, n, h, w, st);
+    case 32: return launch<1, 1, true, 2>(p, x, y, n, h, w, st);
     default: return launch<1, 1, false>(p, x, y, n, h, w, st);
     }
 }

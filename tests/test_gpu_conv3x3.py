@@ -53,12 +53,13 @@ CASES = [
 @pytest.fixture
 def kernel_variant():
     """Forces one form of the stride-1 kernel for the launches of the test:
-    1 = one pixel per lane, row-ahead; 2 = two pixels per lane; 3 = one pixel per lane, entry-ahead."""
+    1 = one pixel per lane, row-ahead; 2 = two pixels per lane; 3 = one pixel per lane, entry-ahead;
+    32 = entry-ahead with the input channels split over two slices of four waves."""
     yield lambda v: S.sbn_force_kernel_form(S.SBN_CONV3X3, v)
     S.sbn_force_kernel_form(S.SBN_CONV3X3, 0)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 32])
 @pytest.mark.parametrize("n,h,w,K,N,go,gi,stride,pct,use_bias,relu,perms", CASES)
 def test_shapes(n, h, w, K, N, go, gi, stride, pct, use_bias, relu, perms, variant, kernel_variant):
     if variant and stride != 1:
