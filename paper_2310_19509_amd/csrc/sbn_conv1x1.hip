@@ -469,11 +469,14 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
     if (K <= 32) return p2 ? launch<2, 1, 32, false, true>(p, x, y, M, st) : launch<1, 2, 32, false, true>(p, x, y, M, st);
     if (K <= 64) return p2 ? launch<2, 1, 64, false, true>(p, x, y, M, st) : launch<1, 2, 64, false, true>(p, x, y, M, st);
     int variant = force;
-    // few pixels: less than one workgroup per CU -> one bundle per workgroup, input channels
-    // split over its waves
+    // few pixels (at most four 64-pixel x one-bundle workgroups per CU) and at least 256 input
+    // channels -> one bundle per workgroup, input channels split over its waves: as many waves as keep the launch within about four waves per SIMD
+    // (256 CUs) and leave every wave at least two sub-chunks (timed on the deep MobileNet layers
+    // at batches 1..32)
     const int n_sub = p->dev.n_chunks32;
-    if (!variant && n_sub >= 4 && ((M + 63) / 64) * ((p->dev.n_bundles + 3) / 4) < 256)
-        variant = n_sub >= 16 ? 516 : n_sub >= 8 ? 508 : 504;
+    const long long wg_split = ((M + 63) / 64) * p->dev.n_bundles;
+    if (!variant && n_sub >= 8 && wg_split <= 1024)
+        variant = n_sub >= 32 && wg_split * 16 <= 4096 ? 516 : n_sub >= 16 && wg_split * 8 <= 4096 ? 508 : 504;
     if (!variant) {
         // 128-pixel tiles with 32-channel chunks halve the per-entry overhead; they pay off
         // when there are still several such tiles per CU (256 CUs)
