@@ -610,6 +610,10 @@ int sbn_pack(const sbn_layer_desc_t* d, int device, sbn_packed_t** out)
         delete p;
         return fail(SBN_ENOMEM, "out of host memory while packing");
     }
+    if (const char* what = check_device_layout(p)) {
+        delete p;
+        return fail(SBN_EINVAL, "internal error: device layout is inconsistent (%s)", what);
+    }
     if (device >= 0) {
         if (int rc = upload_device_layout(p)) {
             delete p;

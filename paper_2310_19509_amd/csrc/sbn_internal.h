@@ -84,6 +84,8 @@ namespace sbn {
 
 // Builds p->dev host arrays from the canonical arrays (no HIP calls).
 void build_device_layout(sbn_packed* p);
+// Invariants of p->dev that the kernels rely on; NULL if they hold, else what is violated.
+const char* check_device_layout(const sbn_packed* p);
 // Uploads p->dev to p->device.  Returns SBN_OK or an error code.
 int upload_device_layout(sbn_packed* p);
 void release_device_layout(sbn_packed* p);

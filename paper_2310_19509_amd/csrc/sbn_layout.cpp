@@ -86,6 +86,46 @@ void build_device_layout(sbn_packed* p)
     std::copy(p->bias.begin(), p->bias.end(), L.bias_padded.begin());
 }
 
+// What the kernels take for granted about the tables: checked once per packed layer, on the
+// host, so that no kernel ever walks a malformed record.  Returns NULL or what is wrong.
+static const char* check_tables(const std::vector<uint32_t>& rec, const std::vector<uint32_t>& wo, int n_bundles,
+                                int n_chunks, int slots, size_t n_entries)
+{
+    if (rec.size() != (size_t)n_bundles * n_chunks * slots || wo.size() != (size_t)n_bundles * (n_chunks + 1))
+        return "table sizes";
+    size_t next = 0;                                   // entries are numbered bundle by bundle, chunk by chunk
+    for (int b = 0; b < n_bundles; ++b)
+        for (int c = 0; c < n_chunks; ++c) {
+            const uint32_t* r = &rec[((size_t)b * n_chunks + c) * slots];
+            int n = 0;
+            while (n < slots && r[n] != 0) ++n;
+            for (int q = n; q < slots; ++q)
+                if (r[q] != 0) return "descriptor after the terminator";
+            for (int q = 0; q < n; ++q) {
+                const uint32_t kb4 = r[q] >> 12, m = r[q] & 0xFFFu;
+                if (kb4 >= (uint32_t)slots || m == 0 || m > 15u) return "descriptor out of range";
+                if (q && kb4 <= (r[q - 1] >> 12)) return "pieces of a record not ascending";
+            }
+            if (wo[(size_t)b * (n_chunks + 1) + c] != next) return "first-entry index";
+            next += (size_t)n;
+            if (wo[(size_t)b * (n_chunks + 1) + c + 1] != next) return "first-entry index of the next chunk";
+        }
+    return next == n_entries ? nullptr : "entry count";
+}
+
+const char* check_device_layout(const sbn_packed* p)
+{
+    const DeviceLayout& L = p->dev;
+    if (L.n_bundles != (p->c_out / 4 + kBundleGroups - 1) / kBundleGroups || L.n_chunks != (p->c_in + kChunk - 1) / kChunk ||
+        L.n_chunks32 != (p->c_in + 31) / 32)
+        return "bundle or chunk count";
+    if (const char* e = check_tables(L.records, L.woff, L.n_bundles, L.n_chunks, kSlots, L.n_entries)) return e;
+    if (const char* e = check_tables(L.records32, L.woff32, L.n_bundles, L.n_chunks32, 8, L.n_entries)) return e;
+    if (L.wts.size() != L.n_entries * (size_t)p->kh * p->kw * kBundleGroups * 16) return "weight array size";
+    if (L.bias_padded.size() != (size_t)L.n_bundles * kBundleChannels) return "bias array size";
+    return nullptr;
+}
+
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 int upload_device_layout(sbn_packed* p)
