@@ -321,6 +321,18 @@ int sbn_pointwise_chain(const sbn_chain_t* c, const float* x, float* y, int n, i
                         void* workspace, size_t workspace_bytes, float* const* layer_outputs,
                         void* stream);
 
+/*
+ * By default a depthwise item directly in front of a 1x1 layer with at most
+ * 128 input and 128 output channels (input channels a multiple of 32) runs
+ * inside that layer's launch: the depthwise result is computed tile by tile in
+ * on-chip memory and never written out (those layers are bound by memory
+ * traffic).  Results agree with the separate launches up to fp32 summation
+ * order inside the depthwise layer.  enable = 0 switches this off for the
+ * chain (every item its own launch); a copy of the depthwise output requested
+ * through layer_outputs switches it off for that pair.
+ */
+int sbn_chain_set_fusion(sbn_chain_t* c, int enable);
+
 void sbn_chain_free(sbn_chain_t* c);
 
 /* ------------------------------------------------------------------ measurement helpers */

@@ -55,6 +55,7 @@ SYMBOLS = {
     "sbn_prune_magnitude": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
     "sbn_retained_l1": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                   C.POINTER(C.c_double)]),
+    "sbn_chain_set_fusion": (C.c_int, [C.c_void_p, C.c_int]),
     "sbn_force_kernel_form": (C.c_int, [C.c_int, C.c_int]),
     "sbn_dw_pattern_groups": (C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_int), C.c_void_p]),
     "sbn_dw_pattern_select": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),

@@ -17,7 +17,7 @@ __all__ = [
     "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_chain_free",
     "sbn_copy_bytes", "dw_item", "sparse_item", "avgpool_item", "stem_item", "SBN_ITEM_STEM3X3",
     "SBN_DW_PATTERN_DENSE", "sbn_dw_pattern_groups", "sbn_dw_pattern_select", "sbn_dw_pattern_apply",
-    "sbn_force_kernel_form", "SBN_K3_PATTERNS", "SBN_K3_PATTERN_DENSE", "sbn_conv3x3_pattern_taps", "sbn_conv3x3_pattern_select",
+    "sbn_force_kernel_form", "sbn_chain_set_fusion", "SBN_K3_PATTERNS", "SBN_K3_PATTERN_DENSE", "sbn_conv3x3_pattern_taps", "sbn_conv3x3_pattern_select",
     "sbn_conv3x3_pattern_apply",
 ]
 
@@ -353,6 +353,11 @@ def sbn_chain_output_shape(c: Chain, n: int, h: int, w: int):
     oh, ow, oc = C.c_int(), C.c_int(), C.c_int()
     _check(_lib.lib().sbn_chain_output_shape(c.handle, n, h, w, C.byref(oh), C.byref(ow), C.byref(oc)))
     return oh.value, ow.value, oc.value
+
+
+def sbn_chain_set_fusion(c: Chain, enable: bool) -> None:
+    """Switch the fused depthwise + small 1x1 launches of a chain on (default) or off."""
+    _check(_lib.lib().sbn_chain_set_fusion(c.handle, 1 if enable else 0))
 
 
 def sbn_pointwise_chain(c: Chain, x, y, n: int, h: int, w: int, workspace, layer_outputs=None, stream=None) -> None:

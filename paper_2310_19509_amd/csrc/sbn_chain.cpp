@@ -22,6 +22,7 @@ struct sbn_chain {
     int device = 0;
     int c_in = 0;
     void* d_blob = nullptr;
+    bool fuse_dw = true;           // run a depthwise item and the small 1x1 layer after it as one launch
 };
 
 namespace {
@@ -264,10 +265,33 @@ int sbn_pointwise_chain(const sbn_chain_t* c, const float* x, float* y, int n, i
     float* buf[2] = {(float*)workspace, (float*)((char*)workspace + half)};
     const float* src = x;
     Shape s{n, h, w, c->c_in};
+    int which = 0;                   // half of the workspace the next launch writes
     for (size_t i = 0; i < c->items.size(); ++i) {
         const sbn_chain::Item& it = c->items[i];
+        // A depthwise layer in front of a small 1x1 layer runs inside that layer's launch (its
+        // output never exists in memory), unless the caller asked for a copy of it.
+        if (c->fuse_dw && it.item == SBN_ITEM_DW3X3 && i + 1 < c->items.size() &&
+            c->items[i + 1].item == SBN_ITEM_SPARSE && dwpw_fusable(c->items[i + 1].packed, it.channels, it.stride) &&
+            !(layer_outputs && layer_outputs[i])) {
+            const sbn_chain::Item& pw = c->items[i + 1];
+            const bool last2 = i + 2 == c->items.size();
+            float* dst2 = last2 ? y : buf[which];
+            const Shape o2 = next_shape(pw, next_shape(it, s));
+            int rc2 = launch_dwpw(pw.packed, src, dst2, it.d_w, it.d_b, it.stride, it.act, (int)s.n, s.h, s.w, stream);
+            if (rc2) return rc2;
+            if (layer_outputs && layer_outputs[i + 1]) {
+                if (o2.bytes() % 16) return fail(SBN_EINVAL, "output of item %zu is not a multiple of 16 bytes", i + 1);
+                rc2 = launch_copy(dst2, layer_outputs[i + 1], o2.bytes(), stream);
+                if (rc2) return rc2;
+            }
+            src = dst2;
+            s = o2;
+            which ^= 1;
+            ++i;
+            continue;
+        }
         const bool last = i + 1 == c->items.size();
-        float* dst = last ? y : buf[i & 1];
+        float* dst = last ? y : buf[which];
         const Shape o = next_shape(it, s);
         int rc = SBN_OK;
         switch (it.item) {
@@ -296,7 +320,16 @@ int sbn_pointwise_chain(const sbn_chain_t* c, const float* x, float* y, int n, i
         }
         src = dst;
         s = o;
+        which ^= 1;
     }
+    return SBN_OK;
+}
+
+int sbn_chain_set_fusion(sbn_chain_t* c, int enable)
+{
+    clear_error();
+    if (!c) return fail(SBN_EINVAL, "sbn_chain_set_fusion: chain is NULL");
+    c->fuse_dw = enable != 0;
     return SBN_OK;
 }
 

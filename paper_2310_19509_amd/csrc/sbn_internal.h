@@ -97,6 +97,10 @@ int launch_dw3x3(const float* x, float* y, const float* w_dev, const float* b_de
                  int c, int stride, int act, void* stream);
 int launch_stem3x3(const float* x, float* y, const float* w_dev, const float* b_dev, int n, int h, int w, int c_in,
                    int c_out, int stride, int act, void* stream);
+// depthwise 3x3 fused into the 1x1 layer that consumes it (small layers only: see dwpw_fusable)
+bool dwpw_fusable(const sbn_packed* p, int channels, int stride);
+int launch_dwpw(const sbn_packed* p, const float* x, float* y, const float* dw_w, const float* dw_b, int dw_stride,
+                int dw_act, int n, int h, int w, void* stream);
 int launch_avgpool(const float* x, float* y, int n, int hw, int c, void* stream);
 int launch_copy(const void* src, void* dst, size_t bytes, void* stream);
 

@@ -24,6 +24,8 @@ int launch_dw3x3(const float*, float*, const float*, const float*, int, int, int
 int launch_stem3x3(const float*, float*, const float*, const float*, int, int, int, int, int, int, int, void*) { return unreachable("stem3x3"); }
 int launch_avgpool(const float*, float*, int, int, int, void*) { return unreachable("avgpool"); }
 int launch_copy(const void*, void*, size_t, void*) { return unreachable("copy"); }
+bool dwpw_fusable(const sbn_packed*, int, int) { return false; }
+int launch_dwpw(const sbn_packed*, const float*, float*, const float*, const float*, int, int, int, int, int, void*) { return unreachable("dwpw"); }
 }  // namespace sbn
 
 static uint64_t g_state = 0x9E3779B97F4A7C15ull;
@@ -147,6 +149,7 @@ static int error_paths()
     CHECK(sbn_force_kernel_form(SBN_CONV1X1, 13) == SBN_EINVAL && sbn_force_kernel_form(SBN_CONV3X3, 32) == SBN_OK &&
           sbn_force_kernel_form(SBN_CONV3X3, 0) == SBN_OK);
     CHECK(std::strlen(sbn_last_error()) == 0);
+    CHECK(sbn_chain_set_fusion(nullptr, 1) == SBN_EINVAL);
     sbn_free(nullptr);
     sbn_chain_free(nullptr);
     return 0;

@@ -288,3 +288,69 @@ def test_depthwise_layer_with_3_9_pattern_groups(c, hw, stride, go):
     assert (wm != 0).sum() < dw_w.size                                              # something was pruned
     y_ref, bound = R.dwconv3x3_nhwc(mid.cpu().numpy(), wm, dw_b[perm], stride=stride, act=R.ACT_RELU)
     assert_within_bound(yd.cpu().numpy(), y_ref, bound, "pattern-pruned depthwise layer")
+
+
+FUSED_CASES = [
+    # n, h, w, K, N, stride, pct, relu_dw, relu_pw, perm
+    (2, 8, 8, 32, 64, 1, 30, True, True, False),        # one tile, one sub-chunk, one column tile
+    (1, 13, 19, 64, 128, 1, 50, True, True, True),      # ragged tiles, two sub-chunks, two column tiles
+    (2, 17, 9, 64, 128, 2, 50, True, False, True),      # stride 2, odd sizes
+    (1, 21, 21, 128, 128, 1, 70, True, True, True),     # four sub-chunks
+    (1, 12, 30, 128, 72, 2, 90, False, True, False),    # stride 2, no ReLU after the depthwise layer, ragged N
+    (3, 1, 1, 32, 8, 1, 0, True, True, False),          # single pixels
+    (1, 9, 9, 96, 24, 1, 100, True, True, False),       # everything pruned: act(bias) everywhere
+]
+
+
+@pytest.mark.parametrize("n,h,w,K,N,stride,pct,relu_dw,relu_pw,perm", FUSED_CASES)
+def test_depthwise_fused_into_small_pointwise_layer(n, h, w, K, N, stride, pct, relu_dw, relu_pw, perm):
+    """A depthwise layer in front of a 1x1 layer with at most 128 channels on either side runs inside
+    that layer's launch.  Checked against the oracle's two layers (the tolerance of the second carries
+    the first's through the 1x1 weights: |err| <= 1e-4 (bound_pw + |W| bound_dw)), and against the
+    same chain with the fusion switched off."""
+    seed = 9700 + K + N + stride + pct
+    dw_w = W.normal_weights(seed, (K, 3, 3), 0.4)
+    dw_b = W.small_bias(seed + 1, K) * 10
+    wt = W.he_weights(seed + 2, N, 1, 1, K)
+    b = W.small_bias(seed + 3, N) * 10
+    po = W.random_permutation(seed + 4, N) if perm else None
+    mask = S.sbn_prune_magnitude(R.permute_weights(wt, po, None), S.SBN_CONV1X1, 4, 4, pct)
+    act_pw = S.SBN_ACT_RELU if relu_pw else S.SBN_ACT_NONE
+    p = S.sbn_pack(S.SBN_CONV1X1, wt, 4, 4, mask=mask, bias=b, perm_out=po, act=act_pw)
+    chain = S.sbn_chain_create([S.dw_item(dw_w, dw_b, stride=stride, act=S.SBN_ACT_RELU if relu_dw else S.SBN_ACT_NONE),
+                                S.sparse_item(p)])
+    oh, ow, oc = S.sbn_chain_output_shape(chain, n, h, w)
+    ws = torch.empty(S.sbn_chain_workspace(chain, n, h, w) // 4, device="cuda")
+    x = W.uniform_activation(seed + 5, (n, h, w, K))
+    xd = torch.from_numpy(x).cuda()
+    y_fused = torch.full((n, oh, ow, oc), float("nan"), device="cuda")
+    S.sbn_pointwise_chain(chain, xd, y_fused, n, h, w, ws)
+    S.sbn_chain_set_fusion(chain, False)
+    y_plain = torch.full((n, oh, ow, oc), float("nan"), device="cuda")
+    S.sbn_pointwise_chain(chain, xd, y_plain, n, h, w, ws)
+    torch.cuda.synchronize()
+
+    mid, bound_dw = R.dwconv3x3_nhwc(x, dw_w, dw_b, stride=stride, act=R.ACT_RELU if relu_dw else R.ACT_NONE)
+    ref, bound_pw = R.sparse_conv_reference(mid, wt, mask, 4, 4, bias=b, perm_out=po, act=act_pw)
+    wm = np.abs(R.apply_mask(R.permute_weights(wt, po, None), mask, 4, 4).reshape(N, K).astype(np.float64))
+    bound = bound_pw + (bound_dw.reshape(-1, K) @ wm.T).reshape(bound_pw.shape)
+    assert_within_bound(y_fused.cpu().numpy(), ref, bound, f"fused {n,h,w,K,N,stride,pct}")
+    assert_within_bound(y_plain.cpu().numpy(), ref, bound, f"separate {n,h,w,K,N,stride,pct}")
+
+
+def test_fusion_is_skipped_when_the_depthwise_output_is_requested():
+    n, h, w, K, N = 1, 10, 10, 32, 32
+    dw_w, dw_b = W.normal_weights(9801, (K, 3, 3), 0.4), W.small_bias(9802, K)
+    wt = W.he_weights(9803, N, 1, 1, K)
+    p = S.sbn_pack(S.SBN_CONV1X1, wt, 4, 4, act=S.SBN_ACT_RELU)
+    chain = S.sbn_chain_create([S.dw_item(dw_w, dw_b, stride=1, act=S.SBN_ACT_RELU), S.sparse_item(p)])
+    ws = torch.empty(S.sbn_chain_workspace(chain, n, h, w) // 4, device="cuda")
+    x = W.uniform_activation(9804, (n, h, w, K))
+    mid = torch.full((n, h, w, K), float("nan"), device="cuda")
+    yd = torch.full((n, h, w, N), float("nan"), device="cuda")
+    S.sbn_pointwise_chain(chain, torch.from_numpy(x).cuda(), yd, n, h, w, ws, layer_outputs=[mid, None])
+    torch.cuda.synchronize()
+    ref_mid, bound_mid = R.dwconv3x3_nhwc(x, dw_w, dw_b, stride=1, act=R.ACT_RELU)
+    assert_within_bound(mid.cpu().numpy(), ref_mid, bound_mid, "depthwise output copy")
+    ref, bound = R.sparse_conv_reference(mid.cpu().numpy(), wt, None, 4, 4, act=R.ACT_RELU)
+    assert_within_bound(yd.cpu().numpy(), ref, bound, "1x1 after the copied depthwise output")
