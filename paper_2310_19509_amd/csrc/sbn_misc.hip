@@ -181,17 +181,27 @@ __global__ __launch_bounds__(256) void stem3x3_fixed_kernel(const float* __restr
     }
 }
 
-// x [n][hw][c] -> y [n][c]; one thread per (image, channel).
+// x [n][hw][c] -> y [n][c].  A workgroup takes one image x 256 channels: thread t owns channels
+// 4*(t%64)..+3 and every fourth pixel starting at t/64 (16-byte loads, all of them independent);
+// the four partial sums meet in LDS and are added in a fixed order.
 __global__ __launch_bounds__(256) void avgpool_kernel(const float* __restrict__ x, float* __restrict__ y, int hw,
-                                                     int c, long long total)
+                                                     int c, int c_tiles)
 {
-    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (t >= total) return;
-    const long long b = t / c;
-    const int ch = (int)(t % c);
-    float s = 0.f;
-    for (int p = 0; p < hw; ++p) s += x[(b * hw + p) * c + ch];
-    y[t] = s / (float)hw;
+    __shared__ __attribute__((aligned(16))) float part[3 * 256];
+    const long long b = blockIdx.x / c_tiles;
+    const int ch = (blockIdx.x % c_tiles) * 256 + (threadIdx.x & 63) * 4;
+    const int q = threadIdx.x >> 6;
+    v4f s = {0.f, 0.f, 0.f, 0.f};
+    if (ch < c)
+        for (int p = q; p < hw; p += 4) s += *(const v4f*)(x + (b * hw + p) * c + ch);
+    if (q) *(v4f*)(part + (q - 1) * 256 + (threadIdx.x & 63) * 4) = s;
+    __syncthreads();
+    if (q == 0 && ch < c) {
+#pragma unroll
+        for (int k = 0; k < 3; ++k) s += *(const v4f*)(part + k * 256 + threadIdx.x * 4);
+        const float r = 1.0f / (float)hw;
+        *(v4f*)(y + b * c + ch) = s * r;
+    }
 }
 
 int check_launch(const char* who)
@@ -257,10 +267,11 @@ int launch_stem3x3(const float* x, float* y, const float* w_dev, const float* b_
 
 int launch_avgpool(const float* x, float* y, int n, int hw, int c, void* stream)
 {
-    const long long total = (long long)n * c;
-    if (total == 0) return SBN_OK;
-    hipLaunchKernelGGL(avgpool_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, x, y,
-                       hw, c, total);
+    if ((long long)n * c * hw == 0) return SBN_OK;
+    if (c % 4) return fail(SBN_ESHAPE, "the average pool needs a multiple of 4 channels (got %d)", c);
+    const int c_tiles = (c + 255) / 256;
+    hipLaunchKernelGGL(avgpool_kernel, dim3((unsigned)((long long)n * c_tiles)), dim3(256), 0, (hipStream_t)stream, x, y,
+                       hw, c, c_tiles);
     return check_launch("avgpool");
 }
 
