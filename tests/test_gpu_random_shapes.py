@@ -60,3 +60,39 @@ def test_random_layers_every_form(seed):
     finally:
         S.sbn_force_kernel_form(S.SBN_CONV1X1, 0)
         S.sbn_force_kernel_form(S.SBN_CONV3X3, 0)
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_depthwise_plus_pointwise_pairs(seed):
+    """Random (depthwise 3x3, small 1x1) pairs through the chain: the fused launch and the two separate
+    launches both within the two-layer tolerance of the oracle (|err| <= 1e-4 (bound_pw + |W| bound_dw))."""
+    rng = np.random.default_rng(seed)
+    for _ in range(25):
+        K, N = int(rng.choice([32, 64, 96, 128])), int(rng.integers(1, 17)) * 8
+        n, h, w = int(rng.integers(1, 4)), int(rng.integers(1, 30)), int(rng.integers(1, 30))
+        stride, pct = int(rng.choice([1, 2])), int(rng.choice([0, 30, 50, 70, 90, 100]))
+        act_dw = S.SBN_ACT_RELU if rng.random() < 0.8 else S.SBN_ACT_NONE
+        act_pw = S.SBN_ACT_RELU if rng.random() < 0.5 else S.SBN_ACT_NONE
+        dw_w = (rng.standard_normal((K, 3, 3)) * 0.4).astype(np.float32)
+        dw_b = (rng.standard_normal(K) * 0.1).astype(np.float32) if rng.random() < 0.8 else None
+        wt = (rng.standard_normal((N, 1, 1, K)) * (2.0 / K) ** 0.5).astype(np.float32)
+        b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+        po = rng.permutation(N).astype(np.int32) if rng.random() < 0.5 else None
+        mask = S.sbn_prune_magnitude(R.permute_weights(wt, po, None), S.SBN_CONV1X1, 4, 4, pct)
+        p = S.sbn_pack(S.SBN_CONV1X1, wt, 4, 4, mask=mask, bias=b, perm_out=po, act=act_pw)
+        chain = S.sbn_chain_create([S.dw_item(dw_w, dw_b, stride=stride, act=act_dw), S.sparse_item(p)])
+        oh, ow, oc = S.sbn_chain_output_shape(chain, n, h, w)
+        ws = torch.empty(S.sbn_chain_workspace(chain, n, h, w) // 4, device="cuda")
+        x = rng.uniform(-1, 1, (n, h, w, K)).astype(np.float32)
+        xd = torch.from_numpy(x).cuda()
+        mid, bound_dw = R.dwconv3x3_nhwc(x, dw_w, dw_b, stride=stride, act=act_dw)
+        ref, bound_pw = R.sparse_conv_reference(mid, wt, mask, 4, 4, bias=b, perm_out=po, act=act_pw)
+        wm = np.abs(R.apply_mask(R.permute_weights(wt, po, None), mask, 4, 4).reshape(N, K).astype(np.float64))
+        bound = bound_pw + (bound_dw.reshape(-1, K) @ wm.T).reshape(bound_pw.shape)
+        for fused in (True, False):
+            S.sbn_chain_set_fusion(chain, fused)
+            yd = torch.full((n, oh, ow, oc), float("nan"), device="cuda")
+            S.sbn_pointwise_chain(chain, xd, yd, n, h, w, ws)
+            torch.cuda.synchronize()
+            assert_within_bound(yd.cpu().numpy(), ref, bound,
+                                f"fused={fused} n,h,w={n,h,w} K={K} N={N} stride={stride} pct={pct}")
