@@ -126,9 +126,30 @@ __global__ __launch_bounds__(256) void stem3x3_kernel(const float* __restrict__ 
     *(v4f*)(y + ((b * oh + oy) * (long long)ow + ox) * c_out + co) = acc;
 }
 
-// The usual stem (3 -> 32 channels): one thread computes all 32 output channels of one output
-// pixel.  Weight indices are compile-time constants, so the weights arrive through scalar loads
-// and are operands of the multiply-adds; the 27 inputs of the window sit in registers.
+// The usual stem (3 -> 32 channels): one lane computes all 32 output channels of one output pixel
+// on the matrix pipe.  The 27 inputs of the window sit in registers; the 27 x 32 weights fill 14
+// registers of the wave ([k][c_out] in memory order: lane l of register r holds element 64 r + l),
+// and one v_mfma_f32_4x4x1 per (input k, group of 4 output channels) broadcasts the four weights
+// from lanes 4b..4b+3 of their register to all 16 blocks: 216 MFMAs per 64 pixels instead of 864
+// multiply-adds per lane, which leaves the kernel bound by its memory traffic.
+template <int ABID>
+__device__ __forceinline__ v4f stem_mfma(float w, float x, v4f c)
+{
+    return __builtin_amdgcn_mfma_f32_4x4x1f32(w, x, c, 4, ABID, 0);
+}
+
+template <int CIN, int COUT, int P>
+__device__ __forceinline__ void stem_pairs(const float (&wreg)[(9 * CIN * COUT + 63) / 64], const float (&xin)[9 * CIN],
+                                           v4f (&acc)[COUT / 4])
+{
+    // pair P = k * (COUT/4) + g lives in block P % 16 of register P / 16
+    if constexpr (P < 9 * CIN * (COUT / 4)) {
+        constexpr int G = P % (COUT / 4), KI = P / (COUT / 4);
+        acc[G] = stem_mfma<P % 16>(wreg[P / 16], xin[KI], acc[G]);
+        stem_pairs<CIN, COUT, P + 1>(wreg, xin, acc);
+    }
+}
+
 template <int CIN, int COUT>
 __global__ __launch_bounds__(256) void stem3x3_fixed_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                            const float* __restrict__ wt,
@@ -136,40 +157,45 @@ __global__ __launch_bounds__(256) void stem3x3_fixed_kernel(const float* __restr
                                                            int ow, int stride, int act, long long total)
 {
     constexpr int LS = COUT + 4;                           // LDS row stride (floats)
+    constexpr int NWR = (9 * CIN * COUT + 63) / 64;        // weight registers
     __shared__ __attribute__((aligned(16))) float tile[256 * LS];
+    const int lane = threadIdx.x & 63;
     const long long t0 = (long long)blockIdx.x * 256;
     const long long t = t0 + threadIdx.x;
-    if (t < total) {
-        const int ox = (int)(t % ow);
-        const int oy = (int)((t / ow) % oh);
-        const long long b = t / ((long long)ow * oh);
-        float xin[9][CIN];
+    float wreg[NWR];
 #pragma unroll
-        for (int k = 0; k < 9; ++k) {
-            const int iy = oy * stride + k / 3 - 1, ix = ox * stride + k % 3 - 1;
-            const bool ok = iy >= 0 && iy < h && ix >= 0 && ix < w;
-            const float* xp = x + ((b * h + (ok ? iy : 0)) * w + (ok ? ix : 0)) * CIN;
+    for (int r = 0; r < NWR; ++r) wreg[r] = r * 64 + lane < 9 * CIN * COUT ? wt[r * 64 + lane] : 0.f;
+    // every lane takes part in the MFMAs; lanes past the last pixel compute pixel total-1 again
+    const long long tc = t < total ? t : total - 1;
+    const int ox = (int)(tc % ow);
+    const int oy = (int)((tc / ow) % oh);
+    const long long b = tc / ((long long)ow * oh);
+    float xin[9 * CIN];
 #pragma unroll
-            for (int ci = 0; ci < CIN; ++ci) {
-                const float v = xp[ci];
-                xin[k][ci] = ok ? v : 0.f;
-            }
+    for (int k = 0; k < 9; ++k) {
+        const int iy = oy * stride + k / 3 - 1, ix = ox * stride + k % 3 - 1;
+        const bool ok = iy >= 0 && iy < h && ix >= 0 && ix < w;
+        const float* xp = x + ((b * h + (ok ? iy : 0)) * w + (ok ? ix : 0)) * CIN;
+#pragma unroll
+        for (int ci = 0; ci < CIN; ++ci) {
+            const float v = xp[ci];
+            xin[k * CIN + ci] = ok ? v : 0.f;
         }
+    }
+    v4f acc[COUT / 4];
 #pragma unroll
-        for (int c0 = 0; c0 < COUT; c0 += 4) {
-            v4f acc = *(const v4f*)(bias + c0);
+    for (int g = 0; g < COUT / 4; ++g) acc[g] = *(const v4f*)(bias + g * 4);
+    stem_pairs<CIN, COUT, 0>(wreg, xin, acc);
 #pragma unroll
-            for (int k = 0; k < 9; ++k)
-#pragma unroll
-                for (int ci = 0; ci < CIN; ++ci) acc += xin[k][ci] * *(const v4f*)(wt + (k * CIN + ci) * COUT + c0);
-            if (act == SBN_ACT_RELU) {
-                acc.x = fmaxf(acc.x, 0.f);
-                acc.y = fmaxf(acc.y, 0.f);
-                acc.z = fmaxf(acc.z, 0.f);
-                acc.w = fmaxf(acc.w, 0.f);
-            }
-            *(v4f*)(tile + threadIdx.x * LS + c0) = acc;
+    for (int g = 0; g < COUT / 4; ++g) {
+        v4f o = acc[g];
+        if (act == SBN_ACT_RELU) {
+            o.x = fmaxf(o.x, 0.f);
+            o.y = fmaxf(o.y, 0.f);
+            o.z = fmaxf(o.z, 0.f);
+            o.w = fmaxf(o.w, 0.f);
         }
+        *(v4f*)(tile + threadIdx.x * LS + g * 4) = o;
     }
     // the workgroup's 256 pixels are contiguous in y: store them as full rows
     __syncthreads();
