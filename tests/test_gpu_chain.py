@@ -354,3 +354,70 @@ def test_fusion_is_skipped_when_the_depthwise_output_is_requested():
     assert_within_bound(mid.cpu().numpy(), ref_mid, bound_mid, "depthwise output copy")
     ref, bound = R.sparse_conv_reference(mid.cpu().numpy(), wt, None, 4, 4, act=R.ACT_RELU)
     assert_within_bound(yd.cpu().numpy(), ref, bound, "1x1 after the copied depthwise output")
+
+
+def test_whole_mobilenet_batch64_full_size_sampled():
+    """Config 4 at its full size and in the launch configuration the benchmark times (batch 64,
+    224 x 224, the first three depthwise layers running inside their 1x1 layers): every launch's output
+    is captured and, for sampled images, compared with the oracle fed with the GPU's previous output;
+    a fused pair is compared with the oracle's two layers under the two-layer tolerance."""
+    import bench
+    chain, meta = bench.build_mobilenet_chain(S, W, 50, max_iters=100)
+    n, hw, imgs = 64, 224, [0, 63]
+    g = torch.Generator(device="cuda").manual_seed(4001)
+    xd = torch.rand((n, hw, hw, 3), device="cuda", generator=g) * 2 - 1
+    shapes, h, c = [], hw, 3
+    for m in meta:
+        if m["kind"] in ("dw", "stem"):
+            h = (h - 1) // m["stride"] + 1
+        if m["kind"] in ("pw", "stem"):
+            c = m["w"].shape[0]
+        if m["kind"] == "pool":
+            h = 1
+        shapes.append((n, h, h, c))
+    fused = [i for i, m in enumerate(meta[:-1])
+             if m["kind"] == "dw" and meta[i + 1]["kind"] == "pw" and meta[i + 1]["w"].shape[3] % 32 == 0
+             and meta[i + 1]["w"].shape[3] <= 128 and meta[i + 1]["w"].shape[0] <= 128]
+    assert len(fused) == 3
+    taps = [None if i in fused else torch.full(s, float("nan"), device="cuda") for i, s in enumerate(shapes)]
+    ws = torch.empty(S.sbn_chain_workspace(chain, n, hw, hw) // 4, device="cuda")
+    yd = torch.empty(n, 1, 1, 1000, device="cuda")
+    S.sbn_pointwise_chain(chain, xd, yd, n, hw, hw, ws, layer_outputs=taps)
+    torch.cuda.synchronize()
+    prev = xd[imgs].cpu().numpy()
+    pending = None                      # a fused depthwise item waiting for its 1x1 layer
+    for i, m in enumerate(meta):
+        if i in fused:
+            pending = m
+            continue
+        out = taps[i][imgs].cpu().numpy()
+        if m["kind"] == "stem":
+            ref, bound = R.conv_nhwc(prev, m["w"], m["b"], stride=m["stride"], pad=1, act=R.ACT_RELU)
+        elif m["kind"] == "dw":
+            w, b = m["w"], m["b"]
+            if m["order"] is not None:
+                w, b = w[m["order"]], b[m["order"]]
+            ref, bound = R.dwconv3x3_nhwc(prev, w, b, stride=m["stride"], act=R.ACT_RELU)
+        elif m["kind"] == "pool":
+            ref, bound = R.avgpool_nhwc(prev)[:, None, None, :], None
+        else:
+            x_in, extra = prev, None
+            if pending is not None:
+                w, b = pending["w"], pending["b"]
+                if pending["order"] is not None:
+                    w, b = w[pending["order"]], b[pending["order"]]
+                x_in, bound_dw = R.dwconv3x3_nhwc(prev, w, b, stride=pending["stride"], act=R.ACT_RELU)
+                wp = R.apply_mask(R.permute_weights(m["w"], m["po"], m["pi"]), m["mask"], m["go"], 4)
+                K = wp.shape[3]
+                extra = bound_dw.reshape(-1, K) @ np.abs(wp.reshape(-1, K).astype(np.float64)).T
+                pending = None
+            ref, bound = R.sparse_conv_reference(x_in, m["w"], m["mask"], m["go"], 4, bias=m["b"], perm_out=m["po"],
+                                                 perm_in=m["pi"], act=m["act"])
+            if extra is not None:
+                bound = bound + extra.reshape(bound.shape)
+        if bound is None:
+            np.testing.assert_allclose(out, ref, rtol=0, atol=1e-5)
+        else:
+            assert_within_bound(out, ref, bound, f"mobilenet batch 64 item {i} ({m['kind']})")
+        prev = out
+    assert torch.equal(taps[-1], yd)
