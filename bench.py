@@ -83,14 +83,14 @@ def run_copy(a, torch, S):
                                    "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": 2.0 * n}}))
 
 
-def build_layers(S, W, batch, pct, go, rearrange):
+def build_layers(S, W, batch, pct, go, rearrange, gi=4):
     """Offline part of the path: rearrangement, magnitude pruning, packing."""
     import numpy as np
     tens = [W.pw_layer_tensors(3000, L, batch, with_x=False) for L in W.MOBILENET_V1_PW]
     n = len(tens)
     t0 = time.perf_counter()
     if rearrange:
-        descs = [dict(kind=S.SBN_CONV1X1, w=t["w"], go=go, gi=4) for t in tens]
+        descs = [dict(kind=S.SBN_CONV1X1, w=t["w"], go=go, gi=gi) for t in tens]
         # every layer runs on its own input here, so no order is propagated between layers
         perms = S.sbn_rearrange(descs, [-1] * n, pct, seed=3000, max_iters=500)
     else:
@@ -98,8 +98,8 @@ def build_layers(S, W, batch, pct, go, rearrange):
     packed = []
     for t, po in zip(tens, perms):
         wp = t["w"] if po is None else np.ascontiguousarray(t["w"][po])
-        mask = S.sbn_prune_magnitude(wp, S.SBN_CONV1X1, go, 4, pct)
-        packed.append(S.sbn_pack(S.SBN_CONV1X1, t["w"], go, 4, mask=mask, bias=t["bias"], perm_out=po,
+        mask = S.sbn_prune_magnitude(wp, S.SBN_CONV1X1, go, gi, pct)
+        packed.append(S.sbn_pack(S.SBN_CONV1X1, t["w"], go, gi, mask=mask, bias=t["bias"], perm_out=po,
                                  act=S.SBN_ACT_RELU, device=0))
     return tens, perms, packed, (time.perf_counter() - t0) * 1e3
 
@@ -404,16 +404,16 @@ def run_sweep(a, torch, S, W):
         return e0.elapsed_time(e1) / steps
 
     rows = []
-    for go in (4, 8):
+    for go, gi in ((4, 4), (8, 4), (8, 8)):          # 4x4 (the paper's choice), 8 filters x 4 channels, 8x8 (Table 1)
         base = None
         for pct in (0, 30, 50, 70, 90):
-            _, _, packed, _ = build_layers(S, W, B, pct, go, pct > 0 and not a.no_rearrange)
+            _, _, packed, _ = build_layers(S, W, B, pct, go, pct > 0 and not a.no_rearrange, gi=gi)
             fl = sum(2.0 * S.sbn_packed_work(p)["macs_per_pixel"] * B * L.hw * L.hw
                      for L, p in zip(W.MOBILENET_V1_PW, packed))
             ms_serial = run(packed, [main_s], a.steps, a.warmup)
             ms_multi = run(packed, side, a.steps, a.warmup)
             base = base or (ms_serial, ms_multi)
-            rows.append(dict(go=go, sparsity=pct, nonzero_gflop=round(fl / 1e9, 2),
+            rows.append(dict(go=go, gi=gi, sparsity=pct, nonzero_gflop=round(fl / 1e9, 2),
                              serial_ms=round(ms_serial, 4), serial_tflops=round(fl / ms_serial / 1e9, 2),
                              serial_speedup_vs_kept=round(base[0] / ms_serial, 3),
                              overlapped_ms=round(ms_multi, 4), overlapped_tflops=round(fl / ms_multi / 1e9, 2),
@@ -427,7 +427,7 @@ def run_sweep(a, torch, S, W):
         "value": next(r["overlapped_speedup_vs_kept"] for r in rows if r["go"] == 4 and r["sparsity"] == 30),
         "unit": "x at 30% sparsity, go=4", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "higher_is_better": True, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"13 MobileNet-v1 pointwise layers, batch {B}, fp32, sparsity 0/30/50/70/90 %, go 4 and 8, gi 4"},
+        "config": {"workload": f"13 MobileNet-v1 pointwise layers, batch {B}, fp32, sparsity 0/30/50/70/90 %, blocks of go x gi = 4x4, 8x4 and 8x8"},
         "rows": rows}))
 
 
