@@ -16,7 +16,11 @@
  *     "device" pointers are HIP device memory on the device the packed layer
  *     was created for; they stay owned by the caller.
  *   - Activations are NHWC fp32, contiguous: x[n][h][w][c].  Weights are OHWI
- *     fp32: w[oc][kh][kw][ic] (Section 3.1; Algorithm 1 "Data").
+ *     fp32: w[oc][kh][kw][ic] (Section 3.1; Algorithm 1 "Data").  Device
+ *     activation pointers (x, y, layer_outputs entries) must be 16-byte aligned
+ *     (the kernels use 16-byte loads and stores): SBN_EINVAL otherwise.
+ *   - No C++ exception leaves the library: running out of host memory inside
+ *     any call is reported as SBN_ENOMEM.
  *   - Run calls (sbn_conv*_sparse, sbn_pointwise_chain) launch kernels on the
  *     stream given (a hipStream_t passed as void*; NULL = the null stream),
  *     never allocate, never synchronise and return right after the launch.
@@ -92,6 +96,8 @@ const char* sbn_last_error(void);
  * Removed count = floor(n_blocks * sparsity_percent / 100); norms are summed
  * in fp64 in (filter, ky, kx, channel) order; ties remove the lower
  * (row-major) block index first.  mask_out: host uint8 [c_out/go][c_in/gi].
+ * Weights holding NaN or infinity have no order of importance: SBN_EINVAL
+ * (the same holds for sbn_retained_l1).
  */
 int sbn_prune_magnitude(const float* w_permuted, int kind, int c_in, int c_out, int go, int gi,
                         int sparsity_percent, uint8_t* mask_out);
@@ -202,6 +208,9 @@ int sbn_rearrange(const sbn_layer_desc_t* layers, int n_layers, const int* paren
  * Steps: validate -> permute filters/channels/bias -> mask (given or implied)
  * -> gather kept blocks row by row.  Pruned weights are dropped; kept blocks
  * are copied bit for bit (signed zeros and denormals included).
+ * A 3x3 layer packed for a device (device >= 0) needs c_in % 4 == 0 (its kernel
+ * stages four channels at a time): SBN_ESHAPE otherwise; host-only packing
+ * (device = -1) has no such limit.
  */
 int sbn_pack(const sbn_layer_desc_t* desc, int device, sbn_packed_t** out);
 
@@ -313,9 +322,11 @@ int sbn_chain_output_shape(const sbn_chain_t* c, int n, int h, int w, int* oh, i
  * Run the chain: x device [n][h][w][c_in of first item], y device
  * [n][oh][ow][oc] in the last item's channel order.  workspace: device
  * memory of at least sbn_chain_workspace bytes, 256-byte aligned, used for
- * the intermediate activations (ping-pong).  If layer_outputs != NULL it is
- * a host array of n_items device pointers; a non-NULL entry i receives a
- * copy of item i's output (for per-layer checks), queued on the same stream.
+ * the intermediate activations (ping-pong).  x, y and the workspace must be
+ * three non-overlapping buffers (SBN_EINVAL otherwise).  If layer_outputs !=
+ * NULL it is a host array of EXACTLY n_items device pointers (one per item of
+ * the chain; the call reads all of them); a non-NULL entry i receives a copy
+ * of item i's output (for per-layer checks), queued on the same stream.
  */
 int sbn_pointwise_chain(const sbn_chain_t* c, const float* x, float* y, int n, int h, int w,
                         void* workspace, size_t workspace_bytes, float* const* layer_outputs,

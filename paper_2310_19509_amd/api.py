@@ -89,9 +89,11 @@ class Packed:
 
 
 class Chain:
-    def __init__(self, handle: int, keep):
+    def __init__(self, handle: int, keep, n_items: int = 0, c_in: int = 0):
         self.handle = handle
         self._keep = keep
+        self.n_items = n_items
+        self.c_in = c_in
 
     def __del__(self):
         try:
@@ -279,11 +281,35 @@ def sbn_free(p: Packed) -> None:
         p.handle = None
 
 
+def _shape_of(p: Packed) -> dict:
+    """Channel counts and stride of a packed layer (asked once, kept with the handle)."""
+    info = getattr(p, "_info", None)
+    if info is None:
+        info = p._info = sbn_packed_info(p)
+    return info
+
+
+def _check_extent(t, elements: int, what: str) -> None:
+    """The C side sees raw addresses: a tensor smaller than the extents given would be read or
+    written out of bounds, so sizes are compared here (raw int addresses are the caller's business)."""
+    if t is not None and not isinstance(t, int) and t.numel() < elements:
+        raise ValueError(f"{what} holds {t.numel()} elements, the extents given need {elements}")
+
+
 def sbn_conv1x1_sparse(p: Packed, x, y, n: int, h: int, w: int, stream=None) -> None:
+    if n > 0 and h > 0 and w > 0:
+        info = _shape_of(p)
+        _check_extent(x, n * h * w * info["c_in"], "x")
+        _check_extent(y, n * h * w * info["c_out"], "y")
     _check(_lib.lib().sbn_conv1x1_sparse(p.handle, _dev_ptr(x), _dev_ptr(y), n, h, w, _stream(stream)))
 
 
 def sbn_conv3x3_sparse(p: Packed, x, y, n: int, h: int, w: int, stream=None) -> None:
+    if n > 0 and h > 0 and w > 0:
+        info = _shape_of(p)
+        s = max(1, info["stride"])
+        _check_extent(x, n * h * w * info["c_in"], "x")
+        _check_extent(y, n * ((h - 1) // s + 1) * ((w - 1) // s + 1) * info["c_out"], "y")
     _check(_lib.lib().sbn_conv3x3_sparse(p.handle, _dev_ptr(x), _dev_ptr(y), n, h, w, _stream(stream)))
 
 
@@ -340,7 +366,10 @@ def sbn_chain_create(items: Sequence[dict], device: int = 0) -> Chain:
             keep.append(it)
     out = C.c_void_p()
     _check(_lib.lib().sbn_chain_create(arr, n, device, C.byref(out)))
-    return Chain(out.value, keep)
+    first = items[0]
+    c_in = (_shape_of(first["packed"])["c_in"] if first["item"] == SBN_ITEM_SPARSE else
+            first["w"].shape[3] if first["item"] == SBN_ITEM_STEM3X3 else first["w"].shape[0])
+    return Chain(out.value, keep, n, c_in)
 
 
 def sbn_chain_workspace(c: Chain, n: int, h: int, w: int) -> int:
@@ -362,8 +391,14 @@ def sbn_chain_set_fusion(c: Chain, enable: bool) -> None:
 
 def sbn_pointwise_chain(c: Chain, x, y, n: int, h: int, w: int, workspace, layer_outputs=None, stream=None) -> None:
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    if n > 0 and h > 0 and w > 0:
+        oh, ow, oc = sbn_chain_output_shape(c, n, h, w)
+        _check_extent(x, n * h * w * c.c_in, "x")
+        _check_extent(y, n * oh * ow * oc, "y")
     lo = None
     if layer_outputs is not None:
+        if len(layer_outputs) != c.n_items:       # the C side reads one pointer per item
+            raise ValueError(f"layer_outputs has {len(layer_outputs)} entries, the chain has {c.n_items} items")
         lo = (C.c_void_p * len(layer_outputs))(*[_dev_ptr(t) for t in layer_outputs])
     _check(_lib.lib().sbn_pointwise_chain(c.handle, _dev_ptr(x), _dev_ptr(y), n, h, w,
                                           None if workspace is None else workspace.data_ptr(), ws_bytes, lo,

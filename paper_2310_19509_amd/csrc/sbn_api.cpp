@@ -15,6 +15,9 @@ static int check_run(const sbn_packed_t* p, int kind, const float* x, const floa
     const long long m = (long long)n * h * w;
     if (m > 0 && (!x || !y)) return fail(SBN_EINVAL, "%s: activation pointer is NULL", who);
     if (m > 0 && x == y) return fail(SBN_EINVAL, "%s: x and y must not overlap", who);
+    // the kernels move activations with 16-byte loads and stores
+    if (m > 0 && (((uintptr_t)x | (uintptr_t)y) & 15u))
+        return fail(SBN_EINVAL, "%s: x and y must be 16-byte aligned", who);
     int cur = -1;
     hipError_t e = hipGetDevice(&cur);
     if (e != hipSuccess) return fail(SBN_EHIP, "hipGetDevice: %s", hipGetErrorString(e));

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <memory>
 #include <new>
 
 #include "sbn_internal.h"
@@ -23,6 +24,10 @@ struct sbn_chain {
     int c_in = 0;
     void* d_blob = nullptr;
     bool fuse_dw = true;           // run a depthwise item and the small 1x1 layer after it as one launch
+    ~sbn_chain()
+    {
+        if (d_blob) (void)hipFree(d_blob);
+    }
 };
 
 namespace {
@@ -76,13 +81,14 @@ size_t max_intermediate(const sbn_chain* c, int n, int h, int w)
 
 extern "C" {
 
-int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn_chain_t** out)
+static int chain_create_impl(const sbn_chain_item_t* items, int n_items, int device, sbn_chain_t** out)
 {
     clear_error();
     if (!items || !out || n_items <= 0) return fail(SBN_EINVAL, "sbn_chain_create: NULL pointer or empty chain");
     *out = nullptr;
     if (device < 0) return fail(SBN_EINVAL, "sbn_chain_create: device must be >= 0");
-    sbn_chain* c = new (std::nothrow) sbn_chain;
+    std::unique_ptr<sbn_chain> holder(new (std::nothrow) sbn_chain);     // freed on every early return
+    sbn_chain* c = holder.get();
     if (!c) return fail(SBN_ENOMEM, "out of host memory");
     c->device = device;
 
@@ -95,13 +101,12 @@ int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn
         it.item = s.item;
         if (s.item == SBN_ITEM_SPARSE) {
             const sbn_packed* p = s.packed;
-            if (!p) { delete c; return fail(SBN_EINVAL, "chain item %d: packed layer is NULL", i); }
-            if (p->device != device) { delete c; return fail(SBN_EINVAL, "chain item %d lives on device %d, chain on %d", i, p->device, device); }
-            if (cur_c >= 0 && p->c_in != cur_c) { delete c; return fail(SBN_ESHAPE, "chain item %d reads %d channels, previous item writes %d", i, p->c_in, cur_c); }
+            if (!p) { return fail(SBN_EINVAL, "chain item %d: packed layer is NULL", i); }
+            if (p->device != device) { return fail(SBN_EINVAL, "chain item %d lives on device %d, chain on %d", i, p->device, device); }
+            if (cur_c >= 0 && p->c_in != cur_c) { return fail(SBN_ESHAPE, "chain item %d reads %d channels, previous item writes %d", i, p->c_in, cur_c); }
             for (int ch = 0; ch < p->c_in; ++ch) {
                 const int32_t want = order.empty() ? ch : order[(size_t)ch];
                 if (p->perm_in[(size_t)ch] != want) {
-                    delete c;
                     return fail(SBN_ESHAPE, "chain item %d: perm_in[%d] = %d but its input arrives with channel %d there", i, ch, p->perm_in[(size_t)ch], want);
                 }
             }
@@ -112,17 +117,15 @@ int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn
         } else if (s.item == SBN_ITEM_DW3X3) {
             if (s.channels <= 0 || s.channels % 4 || !s.dw_w || (s.stride != 1 && s.stride != 2) ||
                 (s.act != SBN_ACT_NONE && s.act != SBN_ACT_RELU)) {
-                delete c;
                 return fail(SBN_EINVAL, "chain item %d: bad depthwise description (channels must be a positive multiple of 4, stride 1 or 2)", i);
             }
-            if (cur_c >= 0 && s.channels != cur_c) { delete c; return fail(SBN_ESHAPE, "chain item %d has %d channels, previous item writes %d", i, s.channels, cur_c); }
+            if (cur_c >= 0 && s.channels != cur_c) { return fail(SBN_ESHAPE, "chain item %d has %d channels, previous item writes %d", i, s.channels, cur_c); }
             if (s.dw_pattern) {
                 std::vector<int> st;
-                if (int rc = dw_group_starts(s.channels, s.dw_go, st)) { delete c; return rc; }
+                if (int rc = dw_group_starts(s.channels, s.dw_go, st)) { return rc; }
                 for (size_t g = 0; g + 1 < st.size(); ++g)
                     if (s.dw_pattern[g] > SBN_DW_PATTERN_DENSE) {
-                        delete c;
-                        return fail(SBN_EINVAL, "chain item %d: pattern id %d of group %zu is not in 0..8", i, s.dw_pattern[g], g);
+                            return fail(SBN_EINVAL, "chain item %d: pattern id %d of group %zu is not in 0..8", i, s.dw_pattern[g], g);
                     }
             }
             if (cur_c < 0) c->c_in = s.channels;
@@ -132,10 +135,9 @@ int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn
             cur_c = s.channels;
             dw_floats += (size_t)10 * s.channels;
         } else if (s.item == SBN_ITEM_STEM3X3) {
-            if (i != 0) { delete c; return fail(SBN_ESHAPE, "the stem convolution must be the first item of a chain"); }
+            if (i != 0) { return fail(SBN_ESHAPE, "the stem convolution must be the first item of a chain"); }
             if (s.channels < 1 || s.channels > 4 || s.c_out <= 0 || s.c_out % 4 || s.c_out > 64 || !s.dw_w ||
                 (s.stride != 1 && s.stride != 2) || (s.act != SBN_ACT_NONE && s.act != SBN_ACT_RELU)) {
-                delete c;
                 return fail(SBN_EINVAL, "chain item %d: bad stem description (c_in 1..4, c_out multiple of 4 and <= 64, stride 1 or 2)", i);
             }
             c->c_in = s.channels;
@@ -146,10 +148,9 @@ int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn
             cur_c = s.c_out;
             dw_floats += (size_t)s.c_out * (9 * s.channels + 1);
         } else if (s.item == SBN_ITEM_AVGPOOL) {
-            if (cur_c < 0) { delete c; return fail(SBN_ESHAPE, "a chain cannot start with the average pool"); }
+            if (cur_c < 0) { return fail(SBN_ESHAPE, "a chain cannot start with the average pool"); }
             it.channels = cur_c;
         } else {
-            delete c;
             return fail(SBN_EINVAL, "chain item %d: unknown item kind %d", i, s.item);
         }
         c->items.push_back(it);
@@ -163,9 +164,9 @@ int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn
         if (e == hipSuccess) e = hipMalloc((void**)&blob, dw_floats * sizeof(float));
         if (e != hipSuccess) {
             (void)hipSetDevice(prev);
-            delete c;
             return fail(e == hipErrorOutOfMemory ? SBN_ENOMEM : SBN_EHIP, "chain parameters: %s", hipGetErrorString(e));
         }
+        c->d_blob = blob;                      // owned by the chain from here on
         std::vector<float> host(dw_floats, 0.0f);
         size_t off = 0;
         std::vector<int32_t> ord;
@@ -212,15 +213,15 @@ int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn
         }
         e = hipMemcpy(blob, host.data(), dw_floats * sizeof(float), hipMemcpyHostToDevice);
         (void)hipSetDevice(prev);
-        if (e != hipSuccess) {
-            (void)hipFree(blob);
-            delete c;
-            return fail(SBN_EHIP, "chain parameters upload: %s", hipGetErrorString(e));
-        }
-        c->d_blob = blob;
+        if (e != hipSuccess) return fail(SBN_EHIP, "chain parameters upload: %s", hipGetErrorString(e));
     }
-    *out = c;
+    *out = holder.release();
     return SBN_OK;
+}
+
+int sbn_chain_create(const sbn_chain_item_t* items, int n_items, int device, sbn_chain_t** out)
+{
+    return guarded("sbn_chain_create", [&]() -> int { return chain_create_impl(items, n_items, device, out); });
 }
 
 int sbn_chain_workspace(const sbn_chain_t* c, int n, int h, int w, size_t* bytes_out)
@@ -251,11 +252,28 @@ int sbn_pointwise_chain(const sbn_chain_t* c, const float* x, float* y, int n, i
     if (n < 0 || h < 0 || w < 0) return fail(SBN_EINVAL, "sbn_pointwise_chain: negative extent");
     if ((long long)n * h * w == 0) return SBN_OK;
     if (!x || !y) return fail(SBN_EINVAL, "sbn_pointwise_chain: activation pointer is NULL");
+    if (((uintptr_t)x | (uintptr_t)y) & 15u) return fail(SBN_EINVAL, "sbn_pointwise_chain: x and y must be 16-byte aligned");
     const size_t half = max_intermediate(c, n, h, w);
     if (c->items.size() > 1) {
         if (!workspace || workspace_bytes < 2 * half)
             return fail(SBN_EINVAL, "sbn_pointwise_chain: workspace of %zu bytes needed, %zu given", 2 * half, workspace_bytes);
         if ((uintptr_t)workspace % 256) return fail(SBN_EINVAL, "sbn_pointwise_chain: workspace must be 256-byte aligned");
+    }
+    {
+        // x, y and the workspace are three separate buffers: a launch reads one and writes another
+        Shape so{n, h, w, c->c_in};
+        for (const auto& it : c->items) so = next_shape(it, so);
+        const Shape si{n, h, w, c->c_in};
+        auto overlap = [](const void* a, size_t na, const void* b, size_t nb) {
+            return (uintptr_t)a < (uintptr_t)b + nb && (uintptr_t)b < (uintptr_t)a + na;
+        };
+        if (overlap(x, si.bytes(), y, so.bytes())) return fail(SBN_EINVAL, "sbn_pointwise_chain: x and y overlap");
+        if (c->items.size() > 1 && (overlap(x, si.bytes(), workspace, 2 * half) || overlap(y, so.bytes(), workspace, 2 * half)))
+            return fail(SBN_EINVAL, "sbn_pointwise_chain: x or y overlaps the workspace");
+        if (layer_outputs)
+            for (size_t i = 0; i < c->items.size(); ++i)
+                if ((uintptr_t)layer_outputs[i] & 15u)
+                    return fail(SBN_EINVAL, "sbn_pointwise_chain: layer_outputs[%zu] is not 16-byte aligned", i);
     }
     int cur = -1;
     hipError_t e = hipGetDevice(&cur);
@@ -335,8 +353,6 @@ int sbn_chain_set_fusion(sbn_chain_t* c, int enable)
 
 void sbn_chain_free(sbn_chain_t* c)
 {
-    if (!c) return;
-    if (c->d_blob) (void)hipFree(c->d_blob);
     delete c;
 }
 

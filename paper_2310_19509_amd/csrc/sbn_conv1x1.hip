@@ -67,6 +67,15 @@ __device__ __forceinline__ void entry_fma(uint32_t m, const v4f& w, const v4f (&
     if (__builtin_expect((m & 8u) != 0, 1)) group_fma<P, NA, Q, 3>(w, xv, acc);
 }
 
+// Lanes of one wave exchange data through LDS without a workgroup barrier (the hardware executes
+// a wave's LDS operations in order).  This keeps the compiler from moving LDS accesses across
+// the exchange point; it emits no instruction.
+__device__ __forceinline__ void wave_lds_order()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 template <int NS>
 struct Record {
     uint32_t d[NS];
@@ -385,7 +394,9 @@ __global__ __launch_bounds__(64 * NW) void conv1x1_splitk_kernel(const float* __
             issue_x(cn);
             load_weights(cn, w_nxt);
             r_nxt = recs[cn];
+            wave_lds_order();                  // rows written by other lanes are read below
             walk(r_cur, w_cur);
+            wave_lds_order();                  // all reads of the tile precede its overwrite
             write_x();
 #pragma unroll
             for (int q4 = 0; q4 < NWL; ++q4) w_cur[q4] = w_nxt[q4];
@@ -394,6 +405,7 @@ __global__ __launch_bounds__(64 * NW) void conv1x1_splitk_kernel(const float* __
     }
 
     // ---- the NW partial results meet in LDS and are added in wave order
+    wave_lds_order();                          // the last staged tile is dead before it is reused
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         v4f o = acc[0][g][0];

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <numeric>
 
@@ -76,6 +77,14 @@ static int check_geometry(int kind, int c_in, int c_out, int go, int gi)
 }
 
 static size_t removed_count(size_t n_blocks, int pct) { return n_blocks * (size_t)pct / 100; }
+
+// Sorting by importance needs a strict weak order: NaN norms have none, so they are refused.
+static bool all_finite(const std::vector<double>& v)
+{
+    for (double x : v)
+        if (!std::isfinite(x)) return false;
+    return true;
+}
 
 // Permuted copy: wp[r][ky][kx][c] = w[perm_out[r]][ky][kx][perm_in[c]].
 static void permute_ohwi(const float* w, int c_out, int taps, int c_in, const int32_t* perm_out,
@@ -300,17 +309,20 @@ int sbn_prune_magnitude(const float* w, int kind, int c_in, int c_out, int go, i
     if (!w || !mask_out) return fail(SBN_EINVAL, "sbn_prune_magnitude: NULL pointer");
     if (pct < 0 || pct > 100) return fail(SBN_EINVAL, "sparsity_percent must be in [0,100] (got %d)", pct);
     if (int rc = check_geometry(kind, c_in, c_out, go, gi)) return rc;
-    const int k = kind == SBN_CONV3X3 ? 3 : 1;
-    std::vector<double> s;
-    block_norms(w, c_out, k, k, c_in, go, gi, s);
-    std::vector<uint32_t> order(s.size());
-    std::iota(order.begin(), order.end(), 0u);
-    std::sort(order.begin(), order.end(),
-              [&](uint32_t a, uint32_t b) { return s[a] < s[b] || (s[a] == s[b] && a < b); });
-    const size_t r = removed_count(s.size(), pct);
-    std::fill(mask_out, mask_out + s.size(), (uint8_t)1);
-    for (size_t i = 0; i < r; ++i) mask_out[order[i]] = 0;
-    return SBN_OK;
+    return guarded("sbn_prune_magnitude", [&]() -> int {
+        const int k = kind == SBN_CONV3X3 ? 3 : 1;
+        std::vector<double> s;
+        block_norms(w, c_out, k, k, c_in, go, gi, s);
+        if (!all_finite(s)) return fail(SBN_EINVAL, "sbn_prune_magnitude: the weights contain NaN or infinity");
+        std::vector<uint32_t> order(s.size());
+        std::iota(order.begin(), order.end(), 0u);
+        std::sort(order.begin(), order.end(),
+                  [&](uint32_t a, uint32_t b) { return s[a] < s[b] || (s[a] == s[b] && a < b); });
+        const size_t r = removed_count(s.size(), pct);
+        std::fill(mask_out, mask_out + s.size(), (uint8_t)1);
+        for (size_t i = 0; i < r; ++i) mask_out[order[i]] = 0;
+        return SBN_OK;
+    });
 }
 
 int sbn_retained_l1(const float* w, int kind, int c_in, int c_out, int go, int gi, int pct, double* out)
@@ -319,14 +331,17 @@ int sbn_retained_l1(const float* w, int kind, int c_in, int c_out, int go, int g
     if (!w || !out) return fail(SBN_EINVAL, "sbn_retained_l1: NULL pointer");
     if (pct < 0 || pct > 100) return fail(SBN_EINVAL, "sparsity_percent must be in [0,100] (got %d)", pct);
     if (int rc = check_geometry(kind, c_in, c_out, go, gi)) return rc;
-    const int k = kind == SBN_CONV3X3 ? 3 : 1;
-    std::vector<double> s;
-    block_norms(w, c_out, k, k, c_in, go, gi, s);
-    std::sort(s.begin(), s.end());
-    double t = 0.0;
-    for (size_t i = removed_count(s.size(), pct); i < s.size(); ++i) t += s[i];
-    *out = t;
-    return SBN_OK;
+    return guarded("sbn_retained_l1", [&]() -> int {
+        const int k = kind == SBN_CONV3X3 ? 3 : 1;
+        std::vector<double> s;
+        block_norms(w, c_out, k, k, c_in, go, gi, s);
+        if (!all_finite(s)) return fail(SBN_EINVAL, "sbn_retained_l1: the weights contain NaN or infinity");
+        std::sort(s.begin(), s.end());
+        double t = 0.0;
+        for (size_t i = removed_count(s.size(), pct); i < s.size(); ++i) t += s[i];
+        *out = t;
+        return SBN_OK;
+    });
 }
 
 // ---- 3:9 pattern group pruning of depthwise kernels (Section 3.2, DwConv3x3)
@@ -352,14 +367,16 @@ int sbn_dw_pattern_groups(int c, int go, int* n_groups_out, int* group_start)
 {
     clear_error();
     if (!n_groups_out) return fail(SBN_EINVAL, "sbn_dw_pattern_groups: NULL pointer");
-    std::vector<int> st;
-    if (int rc = sbn::dw_group_starts(c, go, st)) return rc;
-    *n_groups_out = (int)st.size() - 1;
-    if (group_start) std::copy(st.begin(), st.end(), group_start);
-    return SBN_OK;
+    return guarded("sbn_dw_pattern_groups", [&]() -> int {
+        std::vector<int> st;
+        if (int rc = sbn::dw_group_starts(c, go, st)) return rc;
+        *n_groups_out = (int)st.size() - 1;
+        if (group_start) std::copy(st.begin(), st.end(), group_start);
+        return SBN_OK;
+    });
 }
 
-int sbn_dw_pattern_select(const float* w, int c, int go, const uint8_t* keep_dense, uint8_t* pattern_out)
+static int sbn_dw_pattern_select_impl(const float* w, int c, int go, const uint8_t* keep_dense, uint8_t* pattern_out)
 {
     clear_error();
     if (!w || !pattern_out) return fail(SBN_EINVAL, "sbn_dw_pattern_select: NULL pointer");
@@ -387,7 +404,7 @@ int sbn_dw_pattern_select(const float* w, int c, int go, const uint8_t* keep_den
     return SBN_OK;
 }
 
-int sbn_dw_pattern_apply(const float* w, int c, int go, const uint8_t* pattern, float* w_out)
+static int sbn_dw_pattern_apply_impl(const float* w, int c, int go, const uint8_t* pattern, float* w_out)
 {
     clear_error();
     if (!w || !pattern || !w_out) return fail(SBN_EINVAL, "sbn_dw_pattern_apply: NULL pointer");
@@ -491,7 +508,7 @@ int sbn_conv3x3_pattern_apply(const float* w, int c_out, int c_in, int share, co
     return SBN_OK;
 }
 
-int sbn_rearrange(const sbn_layer_desc_t* layers, int n_layers, const int* parent, const int* keep_output_order,
+static int sbn_rearrange_impl(const sbn_layer_desc_t* layers, int n_layers, const int* parent, const int* keep_output_order,
                   int pct, uint64_t seed, int max_iters, int32_t* const* perm_out)
 {
     clear_error();
@@ -526,7 +543,7 @@ int sbn_rearrange(const sbn_layer_desc_t* layers, int n_layers, const int* paren
     return SBN_OK;
 }
 
-int sbn_pack(const sbn_layer_desc_t* d, int device, sbn_packed_t** out)
+static int sbn_pack_impl(const sbn_layer_desc_t* d, int device, sbn_packed_t** out)
 {
     clear_error();
     if (!d || !out) return fail(SBN_EINVAL, "sbn_pack: NULL pointer");
@@ -542,9 +559,13 @@ int sbn_pack(const sbn_layer_desc_t* d, int device, sbn_packed_t** out)
     if (d->perm_out && !is_permutation(d->perm_out, d->c_out)) return fail(SBN_EPERM, "perm_out is not a permutation of 0..%d", d->c_out - 1);
     if (d->perm_in && !is_permutation(d->perm_in, d->c_in)) return fail(SBN_EPERM, "perm_in is not a permutation of 0..%d", d->c_in - 1);
 
-    sbn_packed* p = new (std::nothrow) sbn_packed;
+    if (d->kind == SBN_CONV3X3 && device >= 0 && d->c_in % 4)
+        return fail(SBN_ESHAPE, "a 3x3 layer that runs on a device needs c_in to be a multiple of 4 (got %d)", d->c_in);
+
+    std::unique_ptr<sbn_packed> holder(new (std::nothrow) sbn_packed);     // freed on every early return
+    sbn_packed* p = holder.get();
     if (!p) return fail(SBN_ENOMEM, "out of host memory");
-    try {
+    {
         p->kind = d->kind;
         p->c_in = d->c_in;
         p->c_out = d->c_out;
@@ -606,21 +627,12 @@ int sbn_pack(const sbn_layer_desc_t* d, int device, sbn_packed_t** out)
             p->row_ptr[(size_t)i + 1] = (uint32_t)p->kidx.size();
         }
         build_device_layout(p);
-    } catch (const std::bad_alloc&) {
-        delete p;
-        return fail(SBN_ENOMEM, "out of host memory while packing");
     }
-    if (const char* what = check_device_layout(p)) {
-        delete p;
+    if (const char* what = check_device_layout(p))
         return fail(SBN_EINVAL, "internal error: device layout is inconsistent (%s)", what);
-    }
-    if (device >= 0) {
-        if (int rc = upload_device_layout(p)) {
-            delete p;
-            return rc;
-        }
-    }
-    *out = p;
+    if (device >= 0)
+        if (int rc = upload_device_layout(p)) return rc;
+    *out = holder.release();
     return SBN_OK;
 }
 
@@ -693,6 +705,29 @@ void sbn_free(sbn_packed_t* p)
     if (!p) return;
     release_device_layout(p);
     delete p;
+}
+
+// ---- entry points whose bodies allocate: no exception leaves the library
+
+int sbn_dw_pattern_select(const float* w, int c, int go, const uint8_t* keep_dense, uint8_t* pattern_out)
+{
+    return guarded("sbn_dw_pattern_select", [&]() -> int { return sbn_dw_pattern_select_impl(w, c, go, keep_dense, pattern_out); });
+}
+
+int sbn_dw_pattern_apply(const float* w, int c, int go, const uint8_t* pattern, float* w_out)
+{
+    return guarded("sbn_dw_pattern_apply", [&]() -> int { return sbn_dw_pattern_apply_impl(w, c, go, pattern, w_out); });
+}
+
+int sbn_rearrange(const sbn_layer_desc_t* layers, int n_layers, const int* parent, const int* keep_output_order,
+                  int pct, uint64_t seed, int max_iters, int32_t* const* perm_out)
+{
+    return guarded("sbn_rearrange", [&]() -> int { return sbn_rearrange_impl(layers, n_layers, parent, keep_output_order, pct, seed, max_iters, perm_out); });
+}
+
+int sbn_pack(const sbn_layer_desc_t* d, int device, sbn_packed_t** out)
+{
+    return guarded("sbn_pack", [&]() -> int { return sbn_pack_impl(d, device, out); });
 }
 
 }  // extern "C"

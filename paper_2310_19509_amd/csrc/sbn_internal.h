@@ -5,6 +5,8 @@
 #include <cstdarg>
 #include <cstddef>
 #include <cstdint>
+#include <exception>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -15,6 +17,20 @@ namespace sbn {
 // ---- error reporting -------------------------------------------------------
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();
+// Runs the body of an extern "C" entry point: no C++ exception may cross the C ABI.
+template <class F>
+int guarded(const char* who, F&& body)
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return fail(SBN_ENOMEM, "%s: out of host memory", who);
+    } catch (const std::exception& e) {
+        return fail(SBN_EINVAL, "%s: %s", who, e.what());
+    } catch (...) {
+        return fail(SBN_EINVAL, "%s: unexpected failure", who);
+    }
+}
 int dw_group_starts(int c, int go, std::vector<int>& start);   // pattern groups of a depthwise layer (+ c at the end)
 int forced_kernel_form(int kind);                              // sbn_force_kernel_form's value, 0 = automatic
 

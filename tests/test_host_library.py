@@ -120,6 +120,23 @@ def test_argument_errors():
     assert _lib.lib().sbn_conv1x1_sparse(None, 16, 32, 1, 1, 1, None) == -1
 
 
+def test_nonfinite_weights_and_device_3x3_channel_rule_are_refused():
+    """Importance has no order with NaN in it; a 3x3 layer packed for a device needs c_in % 4 == 0
+    (refused at pack time, before any GPU call, so this runs without a GPU)."""
+    w = W.he_weights(341, 16, 1, 1, 16)
+    w[3, 0, 0, 5] = np.nan
+    _err(lambda: S.sbn_prune_magnitude(w, S.SBN_CONV1X1, 4, 4, 30), -1)
+    _err(lambda: S.sbn_retained_l1(w, S.SBN_CONV1X1, 4, 4, 30), -1)
+    w[3, 0, 0, 5] = np.inf
+    _err(lambda: S.sbn_prune_magnitude(w, S.SBN_CONV1X1, 4, 4, 30), -1)
+    w3 = W.he_weights(342, 8, 3, 3, 6)
+    _err(lambda: S.sbn_pack(S.SBN_CONV3X3, w3, 4, 2, device=0), -2)
+    assert "multiple of 4" in S.sbn_last_error()
+    p = S.sbn_pack(S.SBN_CONV3X3, w3, 4, 2, device=-1)          # host-only packing has no such limit
+    wt, _ = S.sbn_unpack(p)
+    assert np.array_equal(wt.view(np.uint32), w3.view(np.uint32))
+
+
 # ---------------------------------------------------------------- rearrangement
 
 def _layers(seed, chans, go=4, gi=4):

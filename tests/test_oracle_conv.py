@@ -99,6 +99,47 @@ def test_depthwise_matches_torch_grouped_conv(stride):
     assert bound.shape == y.shape and np.all(bound >= 0)
 
 
+@pytest.mark.parametrize("stride", [1, 2])
+def test_depthwise_bound_is_sum_of_magnitudes(stride):
+    """The depthwise bound is the tolerance scale of every depthwise and fused-pair parity test.
+    Pinned three ways: pure-Python brute force of sum |x||w| over the taps inside the image, the
+    identity bound(x, w) = dwconv(|x|, |w|) without bias, and torch's grouped convolution on the
+    magnitudes.  A ones-kernel on a ones-image counts the taps inside the image (9 / 6 / 4)."""
+    x = W.uniform_activation(54, (2, 5, 4, 8))
+    w = W.normal_weights(55, (8, 3, 3), 0.5)
+    b = W.small_bias(56, 8) * 50            # the bias must not enter the bound
+    _, bound = R.dwconv3x3_nhwc(x, w, b, stride=stride, act=R.ACT_RELU)
+    n, ih, iw, c = x.shape
+    oh, ow = (ih - 1) // stride + 1, (iw - 1) // stride + 1
+    brute = np.zeros((n, oh, ow, c))
+    for bi in range(n):
+        for oy in range(oh):
+            for ox in range(ow):
+                for ch in range(c):
+                    s = 0.0
+                    for ky in range(3):
+                        for kx in range(3):
+                            iy, ix = oy * stride + ky - 1, ox * stride + kx - 1
+                            if 0 <= iy < ih and 0 <= ix < iw:
+                                s += abs(float(x[bi, iy, ix, ch])) * abs(float(w[ch, ky, kx]))
+                    brute[bi, oy, ox, ch] = s
+    np.testing.assert_allclose(bound, brute, rtol=1e-14, atol=0)
+    y_abs, _ = R.dwconv3x3_nhwc(np.abs(x), np.abs(w), None, stride=stride)
+    np.testing.assert_allclose(bound, y_abs, rtol=1e-6)
+    t = torch.nn.functional.conv2d(torch.from_numpy(np.abs(x)).double().permute(0, 3, 1, 2),
+                                   torch.from_numpy(np.abs(w)).double()[:, None], None,
+                                   stride=stride, padding=1, groups=c)
+    np.testing.assert_allclose(bound, t.permute(0, 2, 3, 1).numpy(), rtol=1e-13)
+
+
+def test_depthwise_bound_counts_taps_inside_the_image():
+    ones = np.ones((1, 3, 3, 4), np.float32)
+    _, bound = R.dwconv3x3_nhwc(ones, np.ones((4, 3, 3), np.float32))
+    assert np.array_equal(bound[0, :, :, 0], np.array([[4, 6, 4], [6, 9, 6], [4, 6, 4]], float))
+    _, bound2 = R.dwconv3x3_nhwc(ones, np.ones((4, 3, 3), np.float32), stride=2)
+    assert np.array_equal(bound2[0, :, :, 0], np.array([[4, 4], [4, 4]], float))
+
+
 def test_avgpool_is_mean():
     x = W.uniform_activation(61, (3, 7, 7, 10))
     np.testing.assert_allclose(R.avgpool_nhwc(x), x.astype(np.float64).mean(axis=(1, 2)).astype(np.float32),
