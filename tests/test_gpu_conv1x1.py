@@ -115,7 +115,7 @@ def test_large_m_uses_two_pixel_sets_per_wave():
 def test_zero_pixels_and_argument_errors():
     c = W.config1()
     p = S.sbn_pack(S.SBN_CONV1X1, c["w"], 4, 4, mask=c["mask"])
-    x = torch.zeros(4, 64, device="cuda")
+    x = torch.zeros(8, 64, device="cuda")
     y = torch.zeros(4, 128, device="cuda")
     S.sbn_conv1x1_sparse(p, x, y, 0, 14, 14)          # nothing to do
     with pytest.raises(S.SbnError):
@@ -125,7 +125,7 @@ def test_zero_pixels_and_argument_errors():
     with pytest.raises(S.SbnError):
         S.sbn_conv1x1_sparse(p, x, y, -1, 2, 2)
     with pytest.raises(S.SbnError) as ei:                 # 4-byte offset: not 16-byte aligned
-        S.sbn_conv1x1_sparse(p, torch.zeros(4 * 64 + 1, device="cuda")[1:], y, 1, 2, 2)
+        S.sbn_conv1x1_sparse(p, torch.zeros(8 * 64 + 1, device="cuda")[1:], y, 1, 2, 2)
     assert ei.value.code == -1 and "aligned" in str(ei.value)
     with pytest.raises(ValueError):                       # the binding compares sizes with the extents
         S.sbn_conv1x1_sparse(p, x, y, 1, 3, 3)
