@@ -333,6 +333,25 @@ int sbn_pointwise_chain(const sbn_chain_t* c, const float* x, float* y, int n, i
                         void* stream);
 
 /*
+ * The same run for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * intermediate activations live in a fixed array of SBN_STATIC_WORKSPACE_BYTES
+ * inside the library's code object (one copy per GPU, held until the process
+ * ends) instead of a caller's workspace; x, y and layer_outputs are as above.
+ * The call allocates nothing and frees nothing.  An input whose intermediates
+ * (sbn_chain_workspace) exceed SBN_STATIC_WORKSPACE_BYTES is refused with
+ * SBN_EINVAL before anything is launched.  All calls on one GPU share that
+ * GPU's array: two calls whose kernels may overlap in time (different streams,
+ * different threads) race -- order them on one stream or with events.  The
+ * array needs no clearing between calls (every item overwrites what it later
+ * reads).  The array's address is looked up when a chain is created on the
+ * device, so a run call under stream capture queries nothing.
+ */
+#define SBN_STATIC_WORKSPACE_BYTES (32u << 20)
+int sbn_pointwise_chain_static(const sbn_chain_t* c, const float* x, float* y, int n, int h, int w,
+                               float* const* layer_outputs, void* stream);
+
+/*
  * By default a depthwise item directly in front of a 1x1 layer with at most
  * 128 input and 128 output channels (input channels a multiple of 32) runs
  * inside that layer's launch: the depthwise result is computed tile by tile in

@@ -14,7 +14,8 @@ __all__ = [
     "SBN_ITEM_SPARSE", "SBN_ITEM_DW3X3", "SBN_ITEM_AVGPOOL", "SbnError", "Packed", "Chain",
     "sbn_last_error", "sbn_prune_magnitude", "sbn_retained_l1", "sbn_rearrange", "sbn_pack", "sbn_unpack",
     "sbn_export", "sbn_packed_info", "sbn_packed_work", "sbn_free", "sbn_conv1x1_sparse", "sbn_conv3x3_sparse",
-    "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_chain_free",
+    "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_pointwise_chain_static",
+    "SBN_STATIC_WORKSPACE_BYTES", "sbn_chain_free",
     "sbn_copy_bytes", "dw_item", "sparse_item", "avgpool_item", "stem_item", "SBN_ITEM_STEM3X3",
     "SBN_DW_PATTERN_DENSE", "sbn_dw_pattern_groups", "sbn_dw_pattern_select", "sbn_dw_pattern_apply",
     "sbn_force_kernel_form", "sbn_chain_set_fusion", "SBN_K3_PATTERNS", "SBN_K3_PATTERN_DENSE", "sbn_conv3x3_pattern_taps", "sbn_conv3x3_pattern_select",
@@ -403,6 +404,23 @@ def sbn_pointwise_chain(c: Chain, x, y, n: int, h: int, w: int, workspace, layer
     _check(_lib.lib().sbn_pointwise_chain(c.handle, _dev_ptr(x), _dev_ptr(y), n, h, w,
                                           None if workspace is None else workspace.data_ptr(), ws_bytes, lo,
                                           _stream(stream)))
+
+
+SBN_STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def sbn_pointwise_chain_static(c: Chain, x, y, n: int, h: int, w: int, layer_outputs=None, stream=None) -> None:
+    """sbn_pointwise_chain with the library's built-in workspace: allocates nothing."""
+    if n > 0 and h > 0 and w > 0:
+        oh, ow, oc = sbn_chain_output_shape(c, n, h, w)
+        _check_extent(x, n * h * w * c.c_in, "x")
+        _check_extent(y, n * oh * ow * oc, "y")
+    lo = None
+    if layer_outputs is not None:
+        if len(layer_outputs) != c.n_items:
+            raise ValueError(f"layer_outputs has {len(layer_outputs)} entries, the chain has {c.n_items} items")
+        lo = (C.c_void_p * len(layer_outputs))(*[_dev_ptr(t) for t in layer_outputs])
+    _check(_lib.lib().sbn_pointwise_chain_static(c.handle, _dev_ptr(x), _dev_ptr(y), n, h, w, lo, _stream(stream)))
 
 
 def sbn_chain_free(c: Chain) -> None:

@@ -79,6 +79,113 @@ size_t max_intermediate(const sbn_chain* c, int n, int h, int w)
 
 }  // namespace
 
+namespace sbn {
+
+size_t chain_workspace_bytes(const sbn_chain* c, int n, int h, int w) { return c->items.size() > 1 ? 2 * max_intermediate(c, n, h, w) : 0; }
+int chain_device(const sbn_chain* c) { return c->device; }
+
+// Checks the arguments and queues every item of the chain on `stream`; the intermediate
+// activations alternate between the two halves of `workspace`.  Allocates nothing.
+int run_chain(const sbn_chain* c, const float* x, float* y, int n, int h, int w, void* workspace,
+              size_t workspace_bytes, float* const* layer_outputs, void* stream, const char* who)
+{
+    if (!c) return fail(SBN_EINVAL, "%s: chain is NULL", who);
+    if (n < 0 || h < 0 || w < 0) return fail(SBN_EINVAL, "%s: negative extent", who);
+    if ((long long)n * h * w == 0) return SBN_OK;
+    if (!x || !y) return fail(SBN_EINVAL, "%s: activation pointer is NULL", who);
+    if (((uintptr_t)x | (uintptr_t)y) & 15u) return fail(SBN_EINVAL, "%s: x and y must be 16-byte aligned", who);
+    const size_t half = max_intermediate(c, n, h, w);
+    if (c->items.size() > 1) {
+        if (!workspace || workspace_bytes < 2 * half)
+            return fail(SBN_EINVAL, "%s: workspace of %zu bytes needed, %zu given", who, 2 * half, workspace_bytes);
+        if ((uintptr_t)workspace % 256) return fail(SBN_EINVAL, "%s: workspace must be 256-byte aligned", who);
+    }
+    {
+        // x, y and the workspace are three separate buffers: a launch reads one and writes another
+        Shape so{n, h, w, c->c_in};
+        for (const auto& it : c->items) so = next_shape(it, so);
+        const Shape si{n, h, w, c->c_in};
+        auto overlap = [](const void* a, size_t na, const void* b, size_t nb) {
+            return (uintptr_t)a < (uintptr_t)b + nb && (uintptr_t)b < (uintptr_t)a + na;
+        };
+        if (overlap(x, si.bytes(), y, so.bytes())) return fail(SBN_EINVAL, "%s: x and y overlap", who);
+        if (c->items.size() > 1 && (overlap(x, si.bytes(), workspace, 2 * half) || overlap(y, so.bytes(), workspace, 2 * half)))
+            return fail(SBN_EINVAL, "%s: x or y overlaps the workspace", who);
+        if (layer_outputs)
+            for (size_t i = 0; i < c->items.size(); ++i)
+                if ((uintptr_t)layer_outputs[i] & 15u)
+                    return fail(SBN_EINVAL, "%s: layer_outputs[%zu] is not 16-byte aligned", who, i);
+    }
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return fail(SBN_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (cur != c->device) return fail(SBN_EINVAL, "%s: current device is %d, chain lives on %d", who, cur, c->device);
+
+    float* buf[2] = {(float*)workspace, (float*)((char*)workspace + half)};
+    const float* src = x;
+    Shape s{n, h, w, c->c_in};
+    int which = 0;                   // half of the workspace the next launch writes
+    for (size_t i = 0; i < c->items.size(); ++i) {
+        const sbn_chain::Item& it = c->items[i];
+        // A depthwise layer in front of a small 1x1 layer runs inside that layer's launch (its
+        // output never exists in memory), unless the caller asked for a copy of it.
+        if (c->fuse_dw && it.item == SBN_ITEM_DW3X3 && i + 1 < c->items.size() &&
+            c->items[i + 1].item == SBN_ITEM_SPARSE && dwpw_fusable(c->items[i + 1].packed, it.channels, it.stride) &&
+            !(layer_outputs && layer_outputs[i])) {
+            const sbn_chain::Item& pw = c->items[i + 1];
+            const bool last2 = i + 2 == c->items.size();
+            float* dst2 = last2 ? y : buf[which];
+            const Shape o2 = next_shape(pw, next_shape(it, s));
+            int rc2 = launch_dwpw(pw.packed, src, dst2, it.d_w, it.d_b, it.stride, it.act, (int)s.n, s.h, s.w, stream);
+            if (rc2) return rc2;
+            if (layer_outputs && layer_outputs[i + 1]) {
+                if (o2.bytes() % 16) return fail(SBN_EINVAL, "output of item %zu is not a multiple of 16 bytes", i + 1);
+                rc2 = launch_copy(dst2, layer_outputs[i + 1], o2.bytes(), stream);
+                if (rc2) return rc2;
+            }
+            src = dst2;
+            s = o2;
+            which ^= 1;
+            ++i;
+            continue;
+        }
+        const bool last = i + 1 == c->items.size();
+        float* dst = last ? y : buf[which];
+        const Shape o = next_shape(it, s);
+        int rc = SBN_OK;
+        switch (it.item) {
+        case SBN_ITEM_SPARSE:
+            if (it.packed->kind == SBN_CONV1X1)
+                rc = launch_conv1x1(it.packed, src, dst, s.n * s.h * s.w, stream);
+            else
+                rc = launch_conv3x3(it.packed, src, dst, (int)s.n, s.h, s.w, stream);
+            break;
+        case SBN_ITEM_DW3X3:
+            rc = launch_dw3x3(src, dst, it.d_w, it.d_b, (int)s.n, s.h, s.w, s.c, it.stride, it.act, stream);
+            break;
+        case SBN_ITEM_AVGPOOL:
+            rc = launch_avgpool(src, dst, (int)s.n, s.h * s.w, s.c, stream);
+            break;
+        case SBN_ITEM_STEM3X3:
+            rc = launch_stem3x3(src, dst, it.d_w, it.d_b, (int)s.n, s.h, s.w, it.channels, it.c_out, it.stride, it.act,
+                                stream);
+            break;
+        }
+        if (rc) return rc;
+        if (layer_outputs && layer_outputs[i]) {
+            if (o.bytes() % 16) return fail(SBN_EINVAL, "output of item %zu is not a multiple of 16 bytes", i);
+            rc = launch_copy(dst, layer_outputs[i], o.bytes(), stream);
+            if (rc) return rc;
+        }
+        src = dst;
+        s = o;
+        which ^= 1;
+    }
+    return SBN_OK;
+}
+
+}  // namespace sbn
+
 extern "C" {
 
 static int chain_create_impl(const sbn_chain_item_t* items, int n_items, int device, sbn_chain_t** out)
@@ -215,6 +322,16 @@ static int chain_create_impl(const sbn_chain_item_t* items, int n_items, int dev
         (void)hipSetDevice(prev);
         if (e != hipSuccess) return fail(SBN_EHIP, "chain parameters upload: %s", hipGetErrorString(e));
     }
+    {
+        // set-up for sbn_pointwise_chain_static: the built-in workspace's address on this device
+        int prev = 0;
+        (void)hipGetDevice(&prev);
+        hipError_t e = hipSetDevice(device);
+        if (e != hipSuccess) return fail(SBN_EHIP, "hipSetDevice(%d): %s", device, hipGetErrorString(e));
+        const int rc = static_workspace_init(device);
+        (void)hipSetDevice(prev);
+        if (rc) return rc;
+    }
     *out = holder.release();
     return SBN_OK;
 }
@@ -248,99 +365,7 @@ int sbn_pointwise_chain(const sbn_chain_t* c, const float* x, float* y, int n, i
                         size_t workspace_bytes, float* const* layer_outputs, void* stream)
 {
     clear_error();
-    if (!c) return fail(SBN_EINVAL, "sbn_pointwise_chain: chain is NULL");
-    if (n < 0 || h < 0 || w < 0) return fail(SBN_EINVAL, "sbn_pointwise_chain: negative extent");
-    if ((long long)n * h * w == 0) return SBN_OK;
-    if (!x || !y) return fail(SBN_EINVAL, "sbn_pointwise_chain: activation pointer is NULL");
-    if (((uintptr_t)x | (uintptr_t)y) & 15u) return fail(SBN_EINVAL, "sbn_pointwise_chain: x and y must be 16-byte aligned");
-    const size_t half = max_intermediate(c, n, h, w);
-    if (c->items.size() > 1) {
-        if (!workspace || workspace_bytes < 2 * half)
-            return fail(SBN_EINVAL, "sbn_pointwise_chain: workspace of %zu bytes needed, %zu given", 2 * half, workspace_bytes);
-        if ((uintptr_t)workspace % 256) return fail(SBN_EINVAL, "sbn_pointwise_chain: workspace must be 256-byte aligned");
-    }
-    {
-        // x, y and the workspace are three separate buffers: a launch reads one and writes another
-        Shape so{n, h, w, c->c_in};
-        for (const auto& it : c->items) so = next_shape(it, so);
-        const Shape si{n, h, w, c->c_in};
-        auto overlap = [](const void* a, size_t na, const void* b, size_t nb) {
-            return (uintptr_t)a < (uintptr_t)b + nb && (uintptr_t)b < (uintptr_t)a + na;
-        };
-        if (overlap(x, si.bytes(), y, so.bytes())) return fail(SBN_EINVAL, "sbn_pointwise_chain: x and y overlap");
-        if (c->items.size() > 1 && (overlap(x, si.bytes(), workspace, 2 * half) || overlap(y, so.bytes(), workspace, 2 * half)))
-            return fail(SBN_EINVAL, "sbn_pointwise_chain: x or y overlaps the workspace");
-        if (layer_outputs)
-            for (size_t i = 0; i < c->items.size(); ++i)
-                if ((uintptr_t)layer_outputs[i] & 15u)
-                    return fail(SBN_EINVAL, "sbn_pointwise_chain: layer_outputs[%zu] is not 16-byte aligned", i);
-    }
-    int cur = -1;
-    hipError_t e = hipGetDevice(&cur);
-    if (e != hipSuccess) return fail(SBN_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
-    if (cur != c->device) return fail(SBN_EINVAL, "sbn_pointwise_chain: current device is %d, chain lives on %d", cur, c->device);
-
-    float* buf[2] = {(float*)workspace, (float*)((char*)workspace + half)};
-    const float* src = x;
-    Shape s{n, h, w, c->c_in};
-    int which = 0;                   // half of the workspace the next launch writes
-    for (size_t i = 0; i < c->items.size(); ++i) {
-        const sbn_chain::Item& it = c->items[i];
-        // A depthwise layer in front of a small 1x1 layer runs inside that layer's launch (its
-        // output never exists in memory), unless the caller asked for a copy of it.
-        if (c->fuse_dw && it.item == SBN_ITEM_DW3X3 && i + 1 < c->items.size() &&
-            c->items[i + 1].item == SBN_ITEM_SPARSE && dwpw_fusable(c->items[i + 1].packed, it.channels, it.stride) &&
-            !(layer_outputs && layer_outputs[i])) {
-            const sbn_chain::Item& pw = c->items[i + 1];
-            const bool last2 = i + 2 == c->items.size();
-            float* dst2 = last2 ? y : buf[which];
-            const Shape o2 = next_shape(pw, next_shape(it, s));
-            int rc2 = launch_dwpw(pw.packed, src, dst2, it.d_w, it.d_b, it.stride, it.act, (int)s.n, s.h, s.w, stream);
-            if (rc2) return rc2;
-            if (layer_outputs && layer_outputs[i + 1]) {
-                if (o2.bytes() % 16) return fail(SBN_EINVAL, "output of item %zu is not a multiple of 16 bytes", i + 1);
-                rc2 = launch_copy(dst2, layer_outputs[i + 1], o2.bytes(), stream);
-                if (rc2) return rc2;
-            }
-            src = dst2;
-            s = o2;
-            which ^= 1;
-            ++i;
-            continue;
-        }
-        const bool last = i + 1 == c->items.size();
-        float* dst = last ? y : buf[which];
-        const Shape o = next_shape(it, s);
-        int rc = SBN_OK;
-        switch (it.item) {
-        case SBN_ITEM_SPARSE:
-            if (it.packed->kind == SBN_CONV1X1)
-                rc = launch_conv1x1(it.packed, src, dst, s.n * s.h * s.w, stream);
-            else
-                rc = launch_conv3x3(it.packed, src, dst, (int)s.n, s.h, s.w, stream);
-            break;
-        case SBN_ITEM_DW3X3:
-            rc = launch_dw3x3(src, dst, it.d_w, it.d_b, (int)s.n, s.h, s.w, s.c, it.stride, it.act, stream);
-            break;
-        case SBN_ITEM_AVGPOOL:
-            rc = launch_avgpool(src, dst, (int)s.n, s.h * s.w, s.c, stream);
-            break;
-        case SBN_ITEM_STEM3X3:
-            rc = launch_stem3x3(src, dst, it.d_w, it.d_b, (int)s.n, s.h, s.w, it.channels, it.c_out, it.stride, it.act,
-                                stream);
-            break;
-        }
-        if (rc) return rc;
-        if (layer_outputs && layer_outputs[i]) {
-            if (o.bytes() % 16) return fail(SBN_EINVAL, "output of item %zu is not a multiple of 16 bytes", i);
-            rc = launch_copy(dst, layer_outputs[i], o.bytes(), stream);
-            if (rc) return rc;
-        }
-        src = dst;
-        s = o;
-        which ^= 1;
-    }
-    return SBN_OK;
+    return run_chain(c, x, y, n, h, w, workspace, workspace_bytes, layer_outputs, stream, "sbn_pointwise_chain");
 }
 
 int sbn_chain_set_fusion(sbn_chain_t* c, int enable)

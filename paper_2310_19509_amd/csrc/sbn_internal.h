@@ -120,6 +120,16 @@ int launch_dwpw(const sbn_packed* p, const float* x, float* y, const float* dw_w
 int launch_avgpool(const float* x, float* y, int n, int hw, int c, void* stream);
 int launch_copy(const void* src, void* dst, size_t bytes, void* stream);
 
+// Looks up this device's copy of the built-in chain workspace (sbn_chain_static.hip); the
+// device must be current.
+int static_workspace_init(int device);
+
+// Chain internals shared by the two run entry points (sbn_chain.cpp).
+size_t chain_workspace_bytes(const sbn_chain* c, int n, int h, int w);   // 0 for a one-item chain
+int chain_device(const sbn_chain* c);
+int run_chain(const sbn_chain* c, const float* x, float* y, int n, int h, int w, void* workspace,
+              size_t workspace_bytes, float* const* layer_outputs, void* stream, const char* who);
+
 // Block l1 norms in the exact summation order the pruning rule is defined with.
 void block_norms(const float* w, int c_out, int kh, int kw, int c_in, int go, int gi, std::vector<double>& out);
 bool is_permutation(const int32_t* p, int n);
