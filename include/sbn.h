@@ -269,7 +269,8 @@ int sbn_conv3x3_sparse(const sbn_packed_t* p, const float* x, float* y,
  * every form can be checked on every shape; results never depend on the form
  * beyond summation order.  kind: SBN_CONV1X1 (forms 11, 12, 14, 21, 22: pixels
  * per lane and accumulator sets; 504, 508, 516: 4, 8, 16 waves splitting the
- * input channels) or SBN_CONV3X3 (1, 2, 3: one pixel per lane, two pixels per
+ * input channels; 112, 121: forms 12 / 21 with the last pixel tiles run as
+ * four-wave channel-splitting workgroups inside the same launch) or SBN_CONV3X3 (1, 2, 3: one pixel per lane, two pixels per
  * lane, entry-ahead fetch; 32: entry-ahead with the input channels split over
  * two halves of an eight-wave workgroup).  Layers whose shape leaves no choice (c_in <= 64,
  * c_in not a multiple of 4, stride 2) ignore it.  Unknown values: SBN_EINVAL.

@@ -94,35 +94,23 @@ struct Record {
 // afterwards, and one barrier per chunk publishes them.  The prefetch is
 // unconditional (the last chunk fetches itself again): loads issued under a
 // branch would make the compiler wait for them before the first multiply.
+// One tile of the workgroup form: 64*P pixels x 64 output channels (four bundles, one per wave),
+// all input channels.  lds / lds_b: the workgroup's two activation buffers of 64*P x (KC+4)
+// floats each (lds_b unused when !MULTI).  Called by all 256 threads of the workgroup.
 template <int P, int NA, int KC, bool MULTI, bool VEC>
-__global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ x, float* __restrict__ y,
-                                                      const uint32_t* __restrict__ records,
-                                                      const uint32_t* __restrict__ woff,
-                                                      const float* __restrict__ wts, const float* __restrict__ bias,
-                                                      long long M, int K, int N, int n_bundles, int n_chunks,
-                                                      int n_col_tiles, int n_pix_tiles, int act)
+__device__ __forceinline__ void plain_tile(float* __restrict__ lds, float* __restrict__ lds_b,
+                                           const float* __restrict__ x, float* __restrict__ y,
+                                           const uint32_t* __restrict__ records, const uint32_t* __restrict__ woff,
+                                           const float* __restrict__ wts, const float* __restrict__ bias, long long M,
+                                           int K, int N, int n_bundles, int n_chunks, int pix_tile, int col_tile, int act)
 {
     constexpr int T = 64 * P;                  // pixels per workgroup
     constexpr int NS = KC / 4;                 // descriptors per record (one record per KC channels)
     constexpr int NW = NS / 4;                 // 16-byte weight loads per lane and chunk
     constexpr int XS = KC + 4;                 // staged row stride in floats
-    constexpr int XBUF = T * XS;               // floats per activation buffer
-    constexpr bool DB = MULTI;                 // two activation buffers
-    __shared__ __attribute__((aligned(16))) float lds[XBUF];
-    __shared__ __attribute__((aligned(16))) float lds_b[DB ? XBUF : 4];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-
-    // Workgroup -> (pixel tile, column tile).  Consecutive workgroup ids go to
-    // different XCDs (8 of them, each with its own L2); the column tiles of
-    // one pixel tile get ids that differ by multiples of 8 so that they run on
-    // the same XCD and share the activation tile in its L2.
-    const int id = blockIdx.x;
-    const int xcd = id & 7, j = id >> 3;
-    const int pix_tile = (j / n_col_tiles) * 8 + xcd;
-    const int col_tile = j % n_col_tiles;
-    if (pix_tile >= n_pix_tiles) return;
     const long long pix0 = (long long)pix_tile * T;
     const int bundle = col_tile * 4 + wave;
     const bool active = bundle < n_bundles;
@@ -302,6 +290,34 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
     }
 }
 
+// Workgroup -> (pixel tile, column tile).  Consecutive workgroup ids go to different XCDs (8 of
+// them, each with its own L2); the column tiles of one pixel tile get ids that differ by
+// multiples of 8 so that they run on the same XCD and share the activation tile in its L2.
+__device__ __forceinline__ void xcd_tile(int id, int n_col_tiles, int& pix_tile, int& col_tile)
+{
+    const int xcd = id & 7, j = id >> 3;
+    pix_tile = (j / n_col_tiles) * 8 + xcd;
+    col_tile = j % n_col_tiles;
+}
+
+template <int P, int NA, int KC, bool MULTI, bool VEC>
+__global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                      const uint32_t* __restrict__ records,
+                                                      const uint32_t* __restrict__ woff,
+                                                      const float* __restrict__ wts, const float* __restrict__ bias,
+                                                      long long M, int K, int N, int n_bundles, int n_chunks,
+                                                      int n_col_tiles, int n_pix_tiles, int act)
+{
+    constexpr int XBUF = 64 * P * (KC + 4);    // floats per activation buffer
+    __shared__ __attribute__((aligned(16))) float lds[XBUF];
+    __shared__ __attribute__((aligned(16))) float lds_b[MULTI ? XBUF : 4];
+    int pix_tile, col_tile;
+    xcd_tile(blockIdx.x, n_col_tiles, pix_tile, col_tile);
+    if (pix_tile >= n_pix_tiles) return;
+    plain_tile<P, NA, KC, MULTI, VEC>(lds, lds_b, x, y, records, woff, wts, bias, M, K, N, n_bundles, n_chunks, pix_tile,
+                                      col_tile, act);
+}
+
 // Few-pixel form.  With few pixels (batch 1, deep layers) the workgroup kernel above leaves most
 // of the chip idle: pixel tiles x column tiles is far below the number of CUs while every wave walks
 // all of c_in serially.  Here a workgroup owns 64 pixels x ONE bundle and its NW waves split the
@@ -310,23 +326,21 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
 // LDS operations of one wave execute in order, so no barrier is needed); at the end the NW partial
 // results meet in LDS and are added in wave order, which keeps the sum deterministic.
 // Needs c_in % 4 == 0.
+// lds_pool: NW tiles of 64 x 36 floats, one per wave.  Called by all 64*NW threads of the workgroup.
 template <int NW>
-__global__ __launch_bounds__(64 * NW) void conv1x1_splitk_kernel(const float* __restrict__ x, float* __restrict__ y,
-                                                                 const uint32_t* __restrict__ records,
-                                                                 const uint32_t* __restrict__ woff,
-                                                                 const float* __restrict__ wts,
-                                                                 const float* __restrict__ bias, long long M, int K,
-                                                                 int N, int n_bundles, int n_chunks, int act)
+__device__ __forceinline__ void splitk_tile(float* __restrict__ lds_pool, const float* __restrict__ x,
+                                            float* __restrict__ y, const uint32_t* __restrict__ records,
+                                            const uint32_t* __restrict__ woff, const float* __restrict__ wts,
+                                            const float* __restrict__ bias, long long M, int K, int N, int n_chunks,
+                                            long long pix0, int bundle, int act)
 {
     constexpr int KC = 32, NS = KC / 4, NWL = NS / 4, XS = KC + 4, NA = 2;
     constexpr int NL = 8;                                // 16-byte slots per lane and tile
-    __shared__ __attribute__((aligned(16))) float lds_all[NW][64 * XS];
+    float(*lds_all)[64 * XS] = (float(*)[64 * XS])lds_pool;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     float* lds = lds_all[wave];
-    const int bundle = blockIdx.x % n_bundles;           // neighbouring workgroups share the pixels
-    const long long pix0 = (long long)(blockIdx.x / n_bundles) * 64;
 
     v4f acc[1][4][NA];
 #pragma unroll
@@ -432,6 +446,56 @@ __global__ __launch_bounds__(64 * NW) void conv1x1_splitk_kernel(const float* __
 }
 
 template <int NW>
+__global__ __launch_bounds__(64 * NW) void conv1x1_splitk_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                                 const uint32_t* __restrict__ records,
+                                                                 const uint32_t* __restrict__ woff,
+                                                                 const float* __restrict__ wts,
+                                                                 const float* __restrict__ bias, long long M, int K,
+                                                                 int N, int n_bundles, int n_chunks, int act)
+{
+    __shared__ __attribute__((aligned(16))) float lds_pool[NW * 64 * 36];
+    const int bundle = blockIdx.x % n_bundles;           // neighbouring workgroups share the pixels
+    const long long pix0 = (long long)(blockIdx.x / n_bundles) * 64;
+    splitk_tile<NW>(lds_pool, x, y, records, woff, wts, bias, M, K, N, n_chunks, pix0, bundle, act);
+}
+
+// Mixed form for launches of a few rounds of workgroups.  A launch of W workgroup tiles on C
+// compute units finishes when the busiest unit does: ceil(W / C) tiles, although the work is
+// only W / C.  Here the first n_plain workgroups (a whole number of tiles per compute unit) run
+// the workgroup form on pixel tiles [0, tail_tile0); the pixels after that are covered by
+// workgroups of the few-pixel form (one bundle, input channels split over the four waves), each
+// a quarter of a tile's work per SIMD, which the dispatcher spreads evenly at the end.
+template <int P, int NA, int KC>
+__global__ __launch_bounds__(256) void conv1x1_mixed_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                            const uint32_t* __restrict__ records,
+                                                            const uint32_t* __restrict__ woff,
+                                                            const uint32_t* __restrict__ records32,
+                                                            const uint32_t* __restrict__ woff32,
+                                                            const float* __restrict__ wts,
+                                                            const float* __restrict__ bias, long long M, int K, int N,
+                                                            int n_bundles, int n_chunks, int n_chunks32, int n_col_tiles,
+                                                            int n_plain, long long tail_pix0, int n_tail_tiles, int act)
+{
+    constexpr int XBUF = 64 * P * (KC + 4);
+    constexpr int POOL = 2 * XBUF > 4 * 64 * 36 ? 2 * XBUF : 4 * 64 * 36;
+    __shared__ __attribute__((aligned(16))) float pool[POOL];
+    if ((int)blockIdx.x < n_plain) {
+        int pix_tile, col_tile;
+        xcd_tile(blockIdx.x, n_col_tiles, pix_tile, col_tile);      // n_plain covers whole groups of 8 pixel tiles
+        plain_tile<P, NA, KC, true, true>(pool, pool + XBUF, x, y, records, woff, wts, bias, M, K, N, n_bundles, n_chunks,
+                                          pix_tile, col_tile, act);
+    } else {
+        // the bundles of one pixel tile get ids that differ by multiples of 8: same XCD, shared L2
+        const int id = blockIdx.x - n_plain;
+        const int xcd = id & 7, j = id >> 3;
+        const int tile = (j / n_bundles) * 8 + xcd;
+        if (tile >= n_tail_tiles) return;
+        splitk_tile<4>(pool, x, y, records32, woff32, wts, bias, M, K, N, n_chunks32, tail_pix0 + (long long)tile * 64,
+                       j % n_bundles, act);
+    }
+}
+
+template <int NW>
 int launch_splitk(const sbn_packed* p, const float* x, float* y, long long M, hipStream_t st)
 {
     const sbn::DeviceLayout& L = p->dev;
@@ -462,6 +526,29 @@ int launch(const sbn_packed* p, const float* x, float* y, long long M, hipStream
     return SBN_OK;
 }
 
+// Mixed launch: pixel tiles [0, plain_tiles) (a multiple of 8) in the workgroup form, the pixels
+// after them in the few-pixel form.
+template <int P, int NA, int KC>
+int launch_mixed(const sbn_packed* p, const float* x, float* y, long long M, long long plain_tiles, hipStream_t st)
+{
+    const sbn::DeviceLayout& L = p->dev;
+    const int n_col_tiles = (L.n_bundles + 3) / 4;
+    const long long tail_pix0 = plain_tiles * 64 * P;
+    const long long n_tail_tiles = (M - tail_pix0 + 63) / 64;
+    const long long n_plain = plain_tiles * n_col_tiles;
+    const long long grid = n_plain + ((n_tail_tiles + 7) / 8) * 8 * L.n_bundles;
+    if (plain_tiles % 8 || tail_pix0 > M) return sbn::fail(SBN_EINVAL, "internal error: bad split of a mixed launch");
+    if (grid > 0x7FFFFFFFll) return sbn::fail(SBN_EINVAL, "too many pixels for one launch (%lld)", M);
+    hipLaunchKernelGGL((conv1x1_mixed_kernel<P, NA, KC>), dim3((unsigned)grid), dim3(256), 0, st, x, y,
+                       KC == 64 ? L.d_records : L.d_records32, KC == 64 ? L.d_woff : L.d_woff32, L.d_records32,
+                       L.d_woff32, L.d_wts, L.d_bias, M, p->c_in, p->c_out, L.n_bundles,
+                       KC == 64 ? L.n_chunks : L.n_chunks32, L.n_chunks32, n_col_tiles, (int)n_plain, tail_pix0,
+                       (int)n_tail_tiles, p->act);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return sbn::fail(SBN_EHIP, "conv1x1 launch: %s", hipGetErrorString(e));
+    return SBN_OK;
+}
+
 }  // namespace
 
 namespace sbn {
@@ -480,20 +567,36 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
     const bool p2 = force / 10 == 2;
     if (K <= 32) return p2 ? launch<2, 1, 32, false, true>(p, x, y, M, st) : launch<1, 2, 32, false, true>(p, x, y, M, st);
     if (K <= 64) return p2 ? launch<2, 1, 64, false, true>(p, x, y, M, st) : launch<1, 2, 64, false, true>(p, x, y, M, st);
+    const int cus = p->dev.cus;
     int variant = force;
     // few pixels (at most four 64-pixel x one-bundle workgroups per CU) and at least 256 input
-    // channels -> one bundle per workgroup, input channels split over its waves: as many waves as keep the launch within about four waves per SIMD
-    // (256 CUs) and leave every wave at least two sub-chunks (timed on the deep MobileNet layers
-    // at batches 1..32)
+    // channels -> one bundle per workgroup, input channels split over its waves: as many waves as
+    // keep the launch within about four waves per SIMD and leave every wave at least two
+    // sub-chunks (timed on the deep MobileNet layers at batches 1..32)
     const int n_sub = p->dev.n_chunks32;
     const long long wg_split = ((M + 63) / 64) * p->dev.n_bundles;
-    if (!variant && n_sub >= 8 && wg_split <= 1024)
-        variant = n_sub >= 32 && wg_split * 16 <= 4096 ? 516 : n_sub >= 16 && wg_split * 8 <= 4096 ? 508 : 504;
+    if (!variant && n_sub >= 8 && wg_split <= 4ll * cus)
+        variant = n_sub >= 32 && wg_split <= cus ? 516 : n_sub >= 16 && wg_split <= 2ll * cus ? 508 : 504;
+    const int n_col_tiles = (p->dev.n_bundles + 3) / 4;
     if (!variant) {
         // 128-pixel tiles with 32-channel chunks halve the per-entry overhead; they pay off
-        // when there are still several such tiles per CU (256 CUs)
-        const int n_col_tiles = (p->dev.n_bundles + 3) / 4;
-        variant = ((M + 127) / 128) * n_col_tiles >= 6 * 256 ? 21 : 12;
+        // when there are still several such tiles per CU
+        variant = ((M + 127) / 128) * n_col_tiles >= 6ll * cus ? 21 : 12;
+        // Whole rounds of workgroups only: when the last round would occupy at most half of
+        // the compute units, the pixels of that round go to few-pixel workgroups instead.
+        const int px = variant == 21 ? 128 : 64;
+        const long long tiles = (M + px - 1) / px, w = tiles * n_col_tiles, rem = w % cus;
+        if (rem && 2 * rem <= cus && w > cus && n_sub >= 4) {
+            const long long plain_tiles = (w - rem) / n_col_tiles / 8 * 8;
+            return variant == 21 ? launch_mixed<2, 1, 32>(p, x, y, M, plain_tiles, st)
+                                 : launch_mixed<1, 2, 64>(p, x, y, M, plain_tiles, st);
+        }
+    }
+    if (variant == 112 || variant == 121) {             // forced mixed forms: all but the last pixel tiles plain
+        const int px = variant == 121 ? 128 : 64;
+        const long long plain_tiles = ((M + px - 1) / px - 1) / 8 * 8;
+        return variant == 121 ? launch_mixed<2, 1, 32>(p, x, y, M, plain_tiles, st)
+                              : launch_mixed<1, 2, 64>(p, x, y, M, plain_tiles, st);
     }
     switch (variant) {
     case 11: return launch<1, 1, 64, true, true>(p, x, y, M, st);

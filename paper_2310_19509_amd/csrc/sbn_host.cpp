@@ -290,7 +290,7 @@ const char* sbn_last_error(void) { return sbn::g_err.c_str(); }
 int sbn_force_kernel_form(int kind, int form)
 {
     clear_error();
-    static const int forms1x1[] = {0, 11, 12, 14, 21, 22, 504, 508, 516}, forms3x3[] = {0, 1, 2, 3, 32};
+    static const int forms1x1[] = {0, 11, 12, 14, 21, 22, 112, 121, 504, 508, 516}, forms3x3[] = {0, 1, 2, 3, 32};
     bool ok = false;
     if (kind == SBN_CONV1X1)
         for (int f : forms1x1) ok |= f == form;

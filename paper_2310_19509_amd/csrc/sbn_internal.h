@@ -62,6 +62,7 @@ struct DeviceLayout {
     int n_chunks = 0;                     // ceil(c_in / 64)
     size_t n_entries = 0;
     int n_chunks32 = 0;                   // ceil(c_in / 32)
+    int cus = 256;                        // compute units of the device the layer lives on (set at upload)
     // host staging
     std::vector<uint32_t> records;        // [n_bundles][n_chunks][16]
     std::vector<uint32_t> woff;           // [n_bundles][n_chunks + 1]

@@ -138,6 +138,8 @@ int upload_device_layout(sbn_packed* p)
     int prev = 0;
     (void)hipGetDevice(&prev);
     if ((e = hipSetDevice(p->device)) != hipSuccess) return fail(SBN_EHIP, "hipSetDevice: %s", hipGetErrorString(e));
+    int cus = 0;                           // the launchers size their grids by it
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device) == hipSuccess && cus > 0) L.cus = cus;
 
     // One allocation.  The kernels fetch the weights of a whole record (up to
     // 16 entries) at once, so the weight array carries 16 entries of slack.
