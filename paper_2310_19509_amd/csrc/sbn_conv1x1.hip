@@ -30,6 +30,22 @@
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+// Vector instructions share their issue port with the matrix instructions: a plain VALU
+// instruction costs a SIMD about half of a 4x4x1 MFMA (measured: 32 extra v_add per chunk and
+// wave make a 512 x 512 layer 5 % slower).  So the kernels keep address arithmetic out of the
+// VALU.  Tiles are addressed through buffer descriptors: a scalar base and size (the tile's own
+// bytes, so accesses past the tile's last row return zero / are dropped), a per-lane 32-bit
+// offset that never changes, and a scalar offset that advances from chunk to chunk.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);   // raw, 32-bit words
+}
+__device__ __forceinline__ v4f buf_load(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t scalar_off)
+{
+    return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)scalar_off, 0));
+}
 
 template <int ABID>
 __device__ __forceinline__ v4f mfma_bcast(float w, float x, v4f c)
@@ -133,15 +149,26 @@ __device__ __forceinline__ void plain_tile(float* __restrict__ lds, float* __res
     const float* xtile = x + pix0 * K;
     const int rows_valid = (int)(M - pix0 < T ? M - pix0 : T);
     v4f stage_reg[NL];
+    // VEC: the tile as a buffer of rows_valid rows; a slot's offset is row * K + column (bytes),
+    // the chunk advances the scalar offset.  Rows past the last pixel and, in a ragged last chunk,
+    // channels past the end of the last row lie outside the buffer and read as zero; channels past
+    // c_in of other rows read the next row's first channels, which no entry ever uses.
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(xtile, (uint32_t)rows_valid * (uint32_t)K * 4u);
+    uint32_t xoff[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const int slot = i * 256 + threadIdx.x;
+        xoff[i] = ((uint32_t)(slot / C4) * (uint32_t)K + (uint32_t)(slot % C4) * 4u) * 4u;
+    }
     auto issue_x = [&](int c) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int slot = i * 256 + threadIdx.x;
-            const int row = slot / C4, col = (slot % C4) * 4;
-            const float* rp = xtile + (size_t)(row < rows_valid ? row : rows_valid - 1) * K;
             if (VEC) {
-                stage_reg[i] = *(const v4f*)(rp + min(c * KC + col, K - 4));
+                stage_reg[i] = buf_load(xres, xoff[i], (uint32_t)c * (KC * 4));
             } else {
+                const int slot = i * 256 + threadIdx.x;
+                const int row = slot / C4, col = (slot % C4) * 4;
+                const float* rp = xtile + (size_t)(row < rows_valid ? row : rows_valid - 1) * K;
                 v4f v;
                 for (int q = 0; q < 4; ++q) {
                     const int ch = c * KC + col + q;
@@ -166,11 +193,11 @@ __device__ __forceinline__ void plain_tile(float* __restrict__ lds, float* __res
     // array's slack and are never used.
     const uint32_t* wo = woff + (size_t)bsafe * (n_chunks + 1);
     const Record<NS>* recs = (const Record<NS>*)__builtin_assume_aligned(records, 4 * NS) + (size_t)bsafe * n_chunks;
+    const __amdgpu_buffer_rsrc_t wres = make_rsrc(wts, 0xFFFFFFFFu);     // (the launcher checks the array is below 4 GiB)
     auto load_weights = [&](int c, v4f (&w)[NW]) {
         const uint32_t e0 = __builtin_amdgcn_readfirstlane(wo[c]);
-        const v4f* src = (const v4f*)(wts + (size_t)e0 * 64) + lane;
 #pragma unroll
-        for (int q4 = 0; q4 < NW; ++q4) w[q4] = src[q4 * 64];
+        for (int q4 = 0; q4 < NW; ++q4) w[q4] = buf_load(wres, (uint32_t)lane * 16u + q4 * 1024u, e0 * 256u);
     };
 
     // One chunk: start the loads of the next chunk, multiply the current one out
@@ -278,16 +305,19 @@ __device__ __forceinline__ void plain_tile(float* __restrict__ lds, float* __res
             }
         }
         __syncthreads();
+        // The tile's rows of y as a buffer: rows past the last pixel are dropped by the bounds
+        // check, a thread whose column lies past c_out gets an offset outside the buffer.
+        // (Streaming stores: the output is not read again by this launch; measured 3 % of a
+        // 13-layer pass whose buffers do not fit the last-level cache.)
         const int ch_base = col_tile * 64 + h * KC;
+        const __amdgpu_buffer_rsrc_t yres = make_rsrc(y + pix0 * N, (uint32_t)rows_valid * (uint32_t)N * 4u);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int slot = i * 256 + threadIdx.x;
             const int row = slot / C4, col = (slot % C4) * 4;
-            const long long pix = pix0 + row;
-            // (streaming stores: the output is not read again by this launch; measured 3 % of a
-            // 13-layer pass whose buffers do not fit the last-level cache)
-            if (pix < M && ch_base + col < N)
-                __builtin_nontemporal_store(*(const v4f*)(lds + row * XS + col), (v4f*)(y + pix * N + ch_base + col));
+            const uint32_t off = ch_base + col < N ? ((uint32_t)row * (uint32_t)N + (uint32_t)(ch_base + col)) * 4u : 0xFFFFFFF0u;
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, *(const v4f*)(lds + row * XS + col)), yres,
+                                                   (int)off, 0, 2 /* slc: streaming */);
         }
     }
 }
@@ -355,13 +385,15 @@ __device__ __forceinline__ void splitk_tile(float* __restrict__ lds_pool, const 
     const int rows_valid = (int)(M - pix0 < 64 ? M - pix0 : 64);
     const int scol = (lane & 7) * 4;
     v4f stage_reg[NL];
+    // (addresses as in the workgroup form: the tile is a buffer of rows_valid rows, a per-lane
+    // offset that never changes, the sub-chunk in the scalar offset)
+    const __amdgpu_buffer_rsrc_t xres = make_rsrc(xtile, (uint32_t)rows_valid * (uint32_t)K * 4u);
+    uint32_t xoff[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) xoff[i] = ((uint32_t)(i * 8 + (lane >> 3)) * (uint32_t)K + (uint32_t)scol) * 4u;
     auto issue_x = [&](int c) {
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int row = i * 8 + (lane >> 3);
-            const float* rp = xtile + (size_t)(row < rows_valid ? row : rows_valid - 1) * K;
-            stage_reg[i] = *(const v4f*)(rp + min(c * KC + scol, K - 4));
-        }
+        for (int i = 0; i < NL; ++i) stage_reg[i] = buf_load(xres, xoff[i], (uint32_t)c * (KC * 4));
     };
     auto write_x = [&]() {
 #pragma unroll
@@ -369,11 +401,11 @@ __device__ __forceinline__ void splitk_tile(float* __restrict__ lds_pool, const 
     };
     const uint32_t* wo = woff + (size_t)bundle * (n_chunks + 1);
     const Record<NS>* recs = (const Record<NS>*)__builtin_assume_aligned(records, 4 * NS) + (size_t)bundle * n_chunks;
+    const __amdgpu_buffer_rsrc_t wres = make_rsrc(wts, 0xFFFFFFFFu);
     auto load_weights = [&](int c, v4f (&w)[NWL]) {
         const uint32_t e0 = __builtin_amdgcn_readfirstlane(wo[c]);
-        const v4f* src = (const v4f*)(wts + (size_t)e0 * 64) + lane;
 #pragma unroll
-        for (int q4 = 0; q4 < NWL; ++q4) w[q4] = src[q4 * 64];
+        for (int q4 = 0; q4 < NWL; ++q4) w[q4] = buf_load(wres, (uint32_t)lane * 16u + q4 * 1024u, e0 * 256u);
     };
     const char* lds_lane = (const char*)lds + lane * (XS * 4);
     auto read_x = [&](uint32_t d, v4f (&xv)[1]) { xv[0] = *(const v4f*)(lds_lane + (d >> 8)); };
@@ -559,6 +591,9 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
 {
     hipStream_t st = (hipStream_t)stream;
     const int K = p->c_in;
+    // the kernels address the weights with 32-bit byte offsets
+    if ((p->dev.wts.size() + (size_t)kSlots * 64) * sizeof(float) >= 0xFFFFFFFFull)
+        return fail(SBN_EINVAL, "the layer's device weights exceed 4 GiB");
     const int force = forced_kernel_form(SBN_CONV1X1);  // testing / benchmarking override
     if (K % 4) {
         if (K <= 32) return launch<1, 2, 32, false, false>(p, x, y, M, st);
