@@ -40,6 +40,7 @@
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 constexpr int TH = 8;                  // output tile height (width: 8 * PX)
 constexpr int KC = 32;                 // channels staged at a time
@@ -149,34 +150,40 @@ __global__ __launch_bounds__(256 * SPLIT) void conv3x3_kernel(const float* __res
     // ---- staging: thread t moves 16-byte slots t, t+256, ...; slot = pixel * 8 + column, so a
     //      thread keeps its column and walks pixels t/8, t/8 + 32, ...  Positions outside the
     //      image load some inside position and are replaced by zeros on the way to LDS.
+    // Addresses stay out of the VALU (plain vector instructions share the matrix pipe's issue
+    // port): the image is a buffer, a slot's byte offset in it is computed once, positions outside
+    // the image get an offset outside the buffer and are returned as zeros by the bounds check,
+    // and the sub-chunk advances a scalar offset.
     const float* xi = x + img * H * W * K;
+    const __amdgpu_buffer_rsrc_t xres =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(xi), 0, (int)((uint32_t)H * (uint32_t)W * (uint32_t)K * 4u), 0x00020000);
     const int col4 = (tid & 7) * 4;
-    int goff[NL];                 // element offset of the slot's (clamped) input pixel in the image
-    uint32_t inside = 0;          // bit i: slot i is a real position
+    uint32_t goff[NL];            // byte offset of the slot's input position in the image; outside: 2^31, past any
+                                  // image the launcher admits, and far enough from 2^32 not to wrap with the scalar offset
+    int loff[NL];                 // float offset of the slot in the LDS image, -1: no such slot
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-        int pix = i * 32 + (tid >> 3);
-        pix = pix < NPIX ? pix : NPIX - 1;
-        const int iy = iy0 + pix / IW, ix = ix0 + pix % IW;
-        if (iy >= 0 && iy < H && ix >= 0 && ix < W) inside |= 1u << i;
-        goff[i] = (min(max(iy, 0), H - 1) * W + min(max(ix, 0), W - 1)) * K;
+        const int pix = i * 32 + (tid >> 3);
+        const int r = pix / IW, c = pix % IW;
+        const int iy = iy0 + r, ix = ix0 + c;
+        const bool in_image = pix < NPIX && iy >= 0 && iy < H && ix >= 0 && ix < W;
+        goff[i] = in_image ? (uint32_t)((iy * W + ix) * K + col4) * 4u : 0x80000000u;
+        const int g = PX == 1 && STRIDE == 1 ? c & 7 : (c >> 1) & 7;
+        const int blk = r * IWP + c + (STRIDE == 2 ? (r >> 1) & 1 : 0);
+        loff[i] = pix < NPIX ? blk * 32 + (((col4 >> 2) ^ g) << 2) : -1;
     }
     v4f stage_reg[NL];
+    // (a ragged last sub-chunk reads channels past c_in: the next position's first channels, or
+    // zeros at the image's very end; no entry ever uses them)
     auto issue_x = [&](int sc) {
-        const int ch = min(col4 + sc * KC, K - 4);      // keep the 16-byte read inside the pixel's channels
 #pragma unroll
-        for (int i = 0; i < NL; ++i) stage_reg[i] = *(const v4f*)(xi + goff[i] + ch);
+        for (int i = 0; i < NL; ++i)
+            stage_reg[i] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(xres, (int)goff[i], sc * (KC * 4), 0));
     };
     auto write_x = [&](float* buf) {
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int pix = i * 32 + (tid >> 3);
-            const v4f v = (inside >> i) & 1u ? stage_reg[i] : (v4f){0.f, 0.f, 0.f, 0.f};
-            const int r = pix / IW, c = pix % IW;
-            const int g = PX == 1 && STRIDE == 1 ? c & 7 : (c >> 1) & 7;
-            const int blk = r * IWP + c + (STRIDE == 2 ? (r >> 1) & 1 : 0);
-            if (pix < NPIX) *(v4f*)(buf + blk * 32 + (((col4 >> 2) ^ g) << 2)) = v;
-        }
+        for (int i = 0; i < NL; ++i)
+            if (i + 1 < NL || loff[i] >= 0) *(v4f*)(buf + loff[i]) = stage_reg[i];
     };
 
     // this lane's window origin inside the staged tile
@@ -245,6 +252,11 @@ __global__ __launch_bounds__(256 * SPLIT) void conv3x3_kernel(const float* __res
             };
             auto row = [&](auto kytag, uint32_t m, const float (&w)[WT], const v4f (&xr)[NX]) {
                 constexpr int KY = decltype(kytag)::value;
+                // Each row tests its own copy of the mask with scalar instructions: were the three
+                // rows' tests recognised as the same, the compiler would keep their results in
+                // vector registers and pay VALU instructions (which share the matrix pipe's issue
+                // port) to get them back.
+                asm volatile("" : "+s"(m));
                 // a taken branch costs the wave tens of cycles: keep "present" the fall-through path
                 if (__builtin_expect((m & 1u) != 0, 1)) row_fma<0, KY, PX, STRIDE, NX, WT>(w, xr, acc);
                 if (__builtin_expect((m & 2u) != 0, 1)) row_fma<1, KY, PX, STRIDE, NX, WT>(w, xr, acc);
@@ -259,15 +271,17 @@ __global__ __launch_bounds__(256 * SPLIT) void conv3x3_kernel(const float* __res
             // the sub-chunk's last entry reads some in-tile activations that are not used, and the
             // weights of the first entry of the slice's next sub-chunk (past the last sub-chunk:
             // of some entry, or the array's slack).
-            auto entry = [&](uint32_t d, uint32_t d_nxt, float (&w)[WT], float (&w_nxt)[WT], XW& p, XW& r) {
-                const uint32_t e_fetch = e + 1;     // SPLIT > 1: not used after the sub-chunk's last entry
+            // e_cur: this entry's index, e_fetch: the entry whose first weights are fetched meanwhile
+            // (SPLIT > 1: not used after the sub-chunk's last entry).
+            auto entry = [&](uint32_t d, uint32_t d_nxt, uint32_t e_cur, uint32_t e_fetch, float (&w)[WT],
+                             float (&w_nxt)[WT], XW& p, XW& r) {
                 if constexpr (WT == 3) {
                     // weights and activations both run one row ahead; on exit w_nxt and r hold the
                     // first row of the next entry
-                    load_w(e, 1, w_nxt);
+                    load_w(e_cur, 1, w_nxt);
                     load_x(d, 1, r.r[0]);
                     row(std::integral_constant<int, 0>{}, d, w, p.r[0]);
-                    load_w(e, 2, w);
+                    load_w(e_cur, 2, w);
                     load_x(d, 2, p.r[0]);
                     row(std::integral_constant<int, 1>{}, d, w_nxt, r.r[0]);
                     load_w(e_fetch, 0, w_nxt);
@@ -307,24 +321,22 @@ __global__ __launch_bounds__(256 * SPLIT) void conv3x3_kernel(const float* __res
                     load_x(d_cur, 1, xa.r[1]);
                     load_x(d_cur, 2, xa.r[2]);
                 }
-                // The body is written once and the two register sets are exchanged by name; the
-                // compiler unrolls the loop by two and the exchange costs nothing.  (Unrolling it
-                // by hand, with an exit between the copies, made the accumulators alternate between
-                // two register sets, at eight copies per row and group.)
-                while (mine(d_cur)) {
-                    const uint32_t d_nxt = desc(q + 1);
-                    entry(d_cur, d_nxt, wa, wb, xa, xb);
-                    ++q, ++e;
-                    d_cur = d_nxt;
-#pragma unroll
-                    for (int t = 0; t < WT; ++t) {
-                        const float tw = wa[t];
-                        wa[t] = wb[t];
-                        wb[t] = tw;
-                    }
-                    const XW tx = xa;
-                    xa = xb;
-                    xb = tx;
+                // Entries go in pairs, the second with the two register sets (weights and window in
+                // use / on their way) in exchanged roles, so that nothing is ever copied: plain
+                // moves are VALU instructions and share the matrix pipe's issue port (the one-entry
+                // loop with an exchange by name cost up to 27 moves per entry).  After an odd
+                // number of entries the pair's second half runs on the record's terminator: it
+                // multiplies nothing (no group bit is set) and fetches the same next weights again,
+                // which leaves them where the next sub-chunk expects them.
+                while (true) {
+                    const uint32_t d1 = desc(q + 1);
+                    entry(d_cur, d1, e, e + 1, wa, wb, xa, xb);
+                    const uint32_t d2 = desc(q + 2);
+                    const uint32_t two = mine(d1) ? 1u : 0u;
+                    entry(d1, d2, e + 1, e + 1 + two, wb, wa, xb, xa);
+                    q += 1 + two, e += 1 + two;
+                    d_cur = d2;
+                    if (!(mine(d1) && mine(d2))) break;
                 }
             }
         }
@@ -422,8 +434,8 @@ int launch(const sbn_packed* p, const float* x, float* y, int n, int h, int w, h
     const long long n_pix_tiles = (long long)n * tiles_x * tiles_y;
     const int n_col_tiles = (L.n_bundles + 3) / 4;
     const long long grid = ((n_pix_tiles + 7) / 8) * 8 * n_col_tiles;
-    if ((long long)h * w * p->c_in > 0x7FFFFFFFll)
-        return sbn::fail(SBN_EINVAL, "one image of %d x %d x %d elements is too large for 32-bit offsets", h, w, p->c_in);
+    if ((long long)h * w * p->c_in > 0x1FFFFFFFll)     // 2 GiB per image: byte offsets and the out-of-image mark fit 32 bits
+        return sbn::fail(SBN_EINVAL, "one image of %d x %d x %d elements is too large for 32-bit byte offsets", h, w, p->c_in);
     if (grid > 0x7FFFFFFFll || n_pix_tiles > 0x7FFFFFFFll)
         return sbn::fail(SBN_EINVAL, "too many output tiles for one launch (%lld)", n_pix_tiles);
     hipLaunchKernelGGL((conv3x3_kernel<STRIDE, PX, DEEP, SPLIT>), dim3((unsigned)grid), dim3(256 * SPLIT), 0, st, x, y,
