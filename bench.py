@@ -25,11 +25,13 @@ PEAK_HBM_GBS = 8000.0             # MI355X published HBM3E bandwidth
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--workload", default="pw13", choices=["pw13", "mobilenet", "conv3x3", "sweep", "copy"],
+    ap.add_argument("--workload", default="pw13", choices=["pw13", "mobilenet", "conv3x3", "sweep", "copy", "mfma_roof", "lds_roof", "hbm_read"],
                     help="pw13: the 13 pointwise layers (headline metric); mobilenet: the whole network as one "
                          "chain, batch 64, 50 %% sparsity; conv3x3: ResNet-50-shaped 3x3 layers, batch 32, 70 %%; "
                          "sweep: the pointwise stack at 0/30/50/70/90 %% sparsity and go 4/8 against all groups kept; "
-                         "copy: the library's device copy kernel on 256 MiB (measured HBM roof, counter calibration)")
+                         "copy: the library's device copy kernel on 256 MiB (measured HBM roof, counter calibration); "
+                         "mfma_roof / lds_roof / hbm_read: stand-alone loops that measure what the matrix pipe, LDS and "
+                         "a read-only stream deliver on this machine")
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--batch", type=int, default=64)
@@ -100,6 +102,50 @@ def run_copy(a, torch, S):
                       "config": {"workload": "sbn_copy_bytes, 256 MiB read + 256 MiB written per launch"},
                       "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                    "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": 2.0 * n}}))
+
+
+def measure_roofs(torch, S, which=("mfma", "lds", "read"), reps=5):
+    """What the machine's units deliver, from the library's stand-alone loops (each timed over
+    `reps` launches after two untimed ones): matrix pipe TFLOP/s on v_mfma_f32_4x4x1, LDS GB/s on
+    16-byte reads, GB/s of a read-only stream over 512 MiB."""
+    sink = torch.zeros(64, device="cuda")
+    out = {}
+    if "mfma" in which:
+        flops = [0.0]
+        def run():
+            flops[0] = S.sbn_roof_mfma(20000, sink)
+        ms = time_steps(torch, run, reps, 2)
+        out["mfma_f32_4x4x1_tflops"] = round(flops[0] / (ms * 1e-3) / 1e12, 1)
+    if "lds" in which:
+        nbytes = [0.0]
+        def run():
+            nbytes[0] = S.sbn_roof_lds(4000, sink)
+        ms = time_steps(torch, run, reps, 2)
+        out["lds_read_b128_gbs"] = round(nbytes[0] / (ms * 1e-3) / 1e9, 0)
+    if "read" in which:
+        n = 512 << 20
+        src = torch.ones(n // 4, device="cuda")
+        ms = time_steps(torch, lambda: S.sbn_roof_read(src, n, sink), reps, 2)
+        out["hbm_read_gbs"] = round(n / (ms * 1e-3) / 1e9, 0)
+        del src
+    return out
+
+
+def run_roof(a, torch, S):
+    """One of the stand-alone roof loops as a bench line of its own."""
+    kind = {"mfma_roof": "mfma", "lds_roof": "lds", "hbm_read": "read"}[a.workload]
+    r = measure_roofs(torch, S, (kind,), reps=max(3, min(a.steps, 50)))
+    if kind == "mfma":
+        v, unit, peak, metric, bound = r["mfma_f32_4x4x1_tflops"], "TFLOP/s", PEAK_MFMA_F32_TFLOPS, "fp32 matrix pipe, v_mfma_f32_4x4x1 loop", "mfma"
+    elif kind == "lds":
+        v, unit, peak, metric, bound = r["lds_read_b128_gbs"], "GB/s", None, "LDS 16-byte reads, all compute units", "lds"
+    else:
+        v, unit, peak, metric, bound = r["hbm_read_gbs"], "GB/s", PEAK_HBM_GBS, "read-only stream over 512 MiB of device memory", "hbm"
+    print(json.dumps({"metric": metric, "value": v, "unit": unit, "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+                      "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": a.workload},
+                      "roofline": {"bound": bound, "achieved": v, "peak": peak, "unit": unit,
+                                   "frac": None if peak is None else round(v / peak, 4), "traffic": None}}))
 
 
 def build_layers(S, W, batch, pct, go, rearrange, gi=4):
@@ -378,6 +424,7 @@ def run_conv3x3(a, torch, S, W):
         per.append(r)
     avg_launch_s = sum(r["us"] for r in per) * 1e-6 / len(per)
     ach = sum(flops) / len(layers) / avg_launch_s / 1e12
+    measured = measure_roofs(torch, S)
     out = {
         "metric": "effective GFLOP/s (nonzero FLOPs), ResNet-50-shaped 3x3 layers", "value": round(sum(flops) / (ms * 1e-3) / 1e9, 1),
         "unit": "GFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4),
@@ -389,6 +436,8 @@ def run_conv3x3(a, torch, S, W):
                    "sparsity_percent": pct},
         "roofline": {"bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(ach / PEAK_MFMA_F32_TFLOPS, 4),
+                     "measured_roofs": measured,
+                     "frac_of_measured": round(ach / measured["mfma_f32_4x4x1_tflops"], 4),
                      "traffic": profiled_traffic("conv3x3_r50_b32_rho70_traffic.txt", SOURCES_3X3) if (B, pct, a.go) == (32, 70, 4) else None,
                      "kernel": "conv3x3_kernel (4 launches per step, one per layer; durations from serial single-stream passes)",
                      "avg_launch_us": round(avg_launch_s * 1e6, 2)},
@@ -477,6 +526,8 @@ def main():
         return run_sweep(a, torch, S, W)
     if a.workload == "copy":
         return run_copy(a, torch, S)
+    if a.workload in ("mfma_roof", "lds_roof", "hbm_read"):
+        return run_roof(a, torch, S)
     B = a.batch
     tens, perms, packed, pack_ms = build_layers(S, W, B, a.sparsity, a.go, not a.no_rearrange)
     dense = [] if a.no_dense else [S.sbn_pack(S.SBN_CONV1X1, t["w"], a.go, 4, bias=t["bias"], act=S.SBN_ACT_RELU,
@@ -609,6 +660,10 @@ def main():
         roof = dict(bound="hbm", achieved=round(sum(bytes_alg) / n_launch / avg_launch_s / 1e9, 1),
                     peak=PEAK_HBM_GBS, unit="GB/s")
     roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
+    measured = measure_roofs(torch, S)          # what this machine's units deliver (stand-alone loops)
+    roof["measured_roofs"] = measured
+    roof["frac_of_measured"] = round(roof["achieved"] / (measured["mfma_f32_4x4x1_tflops"] if roof["bound"] == "mfma"
+                                                          else measured["hbm_read_gbs"]), 4)
     roof["traffic"] = traffic
     roof["kernel"] = "conv1x1_kernel (13 launches per step, one per layer; durations from a serial single-stream pass)"
     roof["avg_launch_us"] = round(avg_launch_s * 1e6, 2)

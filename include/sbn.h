@@ -381,6 +381,22 @@ int sbn_packed_work(const sbn_packed_t* p, size_t* nnz_blocks_out, size_t* macs_
  */
 int sbn_copy_bytes(const void* src, void* dst, size_t bytes, void* stream);
 
+/*
+ * What this machine's units deliver, measured with stand-alone loops (no part of
+ * the method): set beside the datasheet roofs when a kernel's share of its
+ * roofline is reported.  `sink` is a device float that no launch ever writes
+ * (it keeps the loops alive).  All three launch on `stream` and return at once.
+ *   sbn_roof_mfma: four waves per SIMD issue `iters` x 16 independent
+ *     v_mfma_f32_4x4x1 (the instruction of the sparse kernels, broadcast operand);
+ *     *flops_out = floating-point operations of the launch.
+ *   sbn_roof_lds:  the same waves read 16 bytes per lane from LDS, `iters` x 16
+ *     times, in the 1x1 kernel's row layout; *bytes_out = bytes read.
+ *   sbn_roof_read: reads `bytes` (a multiple of 16) of device memory once.
+ */
+int sbn_roof_mfma(int iters, float* sink, void* stream, double* flops_out);
+int sbn_roof_lds(int iters, float* sink, void* stream, double* bytes_out);
+int sbn_roof_read(const void* src, size_t bytes, float* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

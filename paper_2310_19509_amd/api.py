@@ -16,7 +16,7 @@ __all__ = [
     "sbn_export", "sbn_packed_info", "sbn_packed_work", "sbn_free", "sbn_conv1x1_sparse", "sbn_conv3x3_sparse",
     "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_pointwise_chain_static",
     "SBN_STATIC_WORKSPACE_BYTES", "sbn_chain_free",
-    "sbn_copy_bytes", "dw_item", "sparse_item", "avgpool_item", "stem_item", "SBN_ITEM_STEM3X3",
+    "sbn_copy_bytes", "sbn_roof_mfma", "sbn_roof_lds", "sbn_roof_read", "dw_item", "sparse_item", "avgpool_item", "stem_item", "SBN_ITEM_STEM3X3",
     "SBN_DW_PATTERN_DENSE", "sbn_dw_pattern_groups", "sbn_dw_pattern_select", "sbn_dw_pattern_apply",
     "sbn_force_kernel_form", "sbn_chain_set_fusion", "SBN_K3_PATTERNS", "SBN_K3_PATTERN_DENSE", "sbn_conv3x3_pattern_taps", "sbn_conv3x3_pattern_select",
     "sbn_conv3x3_pattern_apply",
@@ -431,3 +431,21 @@ def sbn_chain_free(c: Chain) -> None:
 
 def sbn_copy_bytes(src, dst, nbytes: int, stream=None) -> None:
     _check(_lib.lib().sbn_copy_bytes(src.data_ptr(), dst.data_ptr(), nbytes, _stream(stream)))
+
+
+def sbn_roof_mfma(iters: int, sink, stream=None) -> float:
+    """Launches the matrix-pipe loop; returns the floating-point operations of the launch."""
+    out = C.c_double()
+    _check(_lib.lib().sbn_roof_mfma(iters, sink.data_ptr(), _stream(stream), C.byref(out)))
+    return out.value
+
+
+def sbn_roof_lds(iters: int, sink, stream=None) -> float:
+    """Launches the LDS read loop; returns the bytes the launch reads."""
+    out = C.c_double()
+    _check(_lib.lib().sbn_roof_lds(iters, sink.data_ptr(), _stream(stream), C.byref(out)))
+    return out.value
+
+
+def sbn_roof_read(src, nbytes: int, sink, stream=None) -> None:
+    _check(_lib.lib().sbn_roof_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream(stream)))

@@ -456,7 +456,8 @@ int launch_conv3x3(const sbn_packed* p, const float* x, float* y, int n, int h, 
         return fail(SBN_ESHAPE, "3x3 layers need c_in to be a multiple of 4 on the device (got %d)", p->c_in);
     hipStream_t st = (hipStream_t)stream;
     if (p->stride == 2) return launch<2, 1, false>(p, x, y, n, h, w, st);
-    // Form, from timings of ResNet-50-shaped layers at batches 4..128 on a 256-CU part: up to one
+    // Form, from timings of ResNet-50-shaped layers at batches 4..128 (thresholds in workgroups per
+    // compute unit of the device the layer lives on): up to one
     // plain workgroup per CU the waves would sit alone on their SIMDs, so the input channels are
     // split over two slices (entry-ahead fetch); up to two per CU the entry-ahead form; above that
     // two pixels per lane when 16-wide tiles waste no more lanes than 8-wide ones (they need 7 %
@@ -466,7 +467,8 @@ int launch_conv3x3(const sbn_packed* p, const float* x, float* y, int n, int h, 
         const long long col_tiles = (p->dev.n_bundles + 3) / 4;
         const long long tiles1 = (long long)((w + 7) / 8) * ((h + 7) / 8), tiles2 = (long long)((w + 15) / 16) * ((h + 7) / 8);
         const long long wg1 = n * tiles1 * col_tiles;
-        form = wg1 <= 256 ? 32 : wg1 <= 512 ? 3 : w > 8 && tiles2 * 2 * 93 < tiles1 * 100 ? 2 : 1;
+        const long long cus = p->dev.cus;
+        form = wg1 <= cus ? 32 : wg1 <= 2 * cus ? 3 : w > 8 && tiles2 * 2 * 93 < tiles1 * 100 ? 2 : 1;
     }
     switch (form) {
     case 2: return launch<1, 2, false>(p, x, y, n, h, w, st);
