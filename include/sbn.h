@@ -189,16 +189,39 @@ int sbn_conv3x3_pattern_apply(const float* w, int c_out, int c_in, int share, co
  * identity (use it for the network's last layer unless its consumer absorbs
  * the order).  keep_output_order may be NULL (= all zero).
  *
- * The search is a deterministic, seeded, bounded hill climb over swaps of two
- * filters of different groups (at most max_iters candidate swaps per layer;
- * for c_out <= 8 every canonical grouping is enumerated instead); a swap is
- * kept only if the objective strictly increases, so the result is never worse
- * than the identity.  Results are in canonical form: filters ascending inside
- * each group, groups ordered by first filter.
+ * The search is deterministic, seeded and bounded: swaps of two filters of
+ * different groups, at most max_iters candidates per tensor; a swap is kept only
+ * if the objective strictly increases; after c_out rejected candidates in a row
+ * the search restarts from the best order so far with two random swaps applied;
+ * the best order seen is returned, so the result is never worse than the
+ * identity.  Layers with at most 20 000 canonical groupings (12 filters in
+ * groups of 4, 16 in groups of 8) are searched exhaustively instead.  Results
+ * are in canonical form: filters ascending inside each group, groups ordered by
+ * first filter.
  */
 int sbn_rearrange(const sbn_layer_desc_t* layers, int n_layers, const int* parent,
                   const int* keep_output_order, int sparsity_percent, uint64_t seed, int max_iters,
                   int32_t* const* perm_per_layer_out);
+
+/*
+ * The same for any graph (Section 3.4: the rearrangement is propagated through
+ * the whole network).  Channel orders belong to TENSORS: layer l reads tensor
+ * in_tensor[l] and writes tensor out_tensor[l] (numbers in 0..n_tensors-1).
+ * Several layers may write the same tensor -- the branches of a residual sum,
+ * or a skip connection, which makes a block's output share the order of its
+ * input -- and then share one filter order, found by maximising the SUM of
+ * their retained importances.  Tensors are decided in increasing number; a
+ * layer's channels count in the order of its input tensor if that tensor has a
+ * lower number than the one being decided, in original order otherwise.  A
+ * tensor no layer writes (a network input) and every tensor with
+ * tensor_fixed[t] != 0 (network outputs; tensor_fixed may be NULL) keep the
+ * identity.  perm_per_tensor_out[t]: int32 [channels of tensor t], caller-
+ * allocated; pack layer l with perm_in = order of in_tensor[l], perm_out = order
+ * of out_tensor[l].  All layers that write a tensor must agree on c_out and go.
+ */
+int sbn_rearrange_graph(const sbn_layer_desc_t* layers, int n_layers, const int* in_tensor, const int* out_tensor,
+                        int n_tensors, const int* tensor_fixed, int sparsity_percent, uint64_t seed, int max_iters,
+                        int32_t* const* perm_per_tensor_out);
 
 /*
  * Pack one layer into the group-sparse format (Algorithm 1's "sparse info":

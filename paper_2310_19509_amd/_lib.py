@@ -65,6 +65,8 @@ SYMBOLS = {
     "sbn_conv3x3_pattern_apply": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "sbn_rearrange": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int,
                                 C.c_uint64, C.c_int, C.POINTER(C.c_void_p)]),
+    "sbn_rearrange_graph": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int,
+                                      C.POINTER(C.c_int), C.c_int, C.c_uint64, C.c_int, C.POINTER(C.c_void_p)]),
     "sbn_pack": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_void_p)]),
     "sbn_unpack": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "sbn_export": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,

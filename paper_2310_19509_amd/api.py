@@ -12,7 +12,7 @@ from ._lib import ChainItem, LayerDesc
 __all__ = [
     "SBN_CONV1X1", "SBN_CONV3X3", "SBN_ACT_NONE", "SBN_ACT_RELU",
     "SBN_ITEM_SPARSE", "SBN_ITEM_DW3X3", "SBN_ITEM_AVGPOOL", "SbnError", "Packed", "Chain",
-    "sbn_last_error", "sbn_prune_magnitude", "sbn_retained_l1", "sbn_rearrange", "sbn_pack", "sbn_unpack",
+    "sbn_last_error", "sbn_prune_magnitude", "sbn_retained_l1", "sbn_rearrange", "sbn_rearrange_graph", "sbn_pack", "sbn_unpack",
     "sbn_export", "sbn_packed_info", "sbn_packed_work", "sbn_free", "sbn_conv1x1_sparse", "sbn_conv3x3_sparse",
     "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_pointwise_chain_static",
     "SBN_STATIC_WORKSPACE_BYTES", "sbn_chain_free",
@@ -224,6 +224,31 @@ def sbn_rearrange(layers: Sequence[dict], parent: Sequence[int], sparsity_percen
     perms = [np.empty(descs[i].c_out, dtype=np.int32) for i in range(n)]
     pp = (C.c_void_p * n)(*[p.ctypes.data for p in perms])
     _check(_lib.lib().sbn_rearrange(descs, n, par, koo, sparsity_percent, seed, max_iters, pp))
+    return perms
+
+
+def sbn_rearrange_graph(layers: Sequence[dict], in_tensor: Sequence[int], out_tensor: Sequence[int], n_tensors: int,
+                        sparsity_percent: int, seed: int = 0, max_iters: int = 2000,
+                        tensor_fixed: Optional[Sequence[int]] = None) -> List[np.ndarray]:
+    """layers: dicts with kind, w, go, gi; layer l reads tensor in_tensor[l] and writes out_tensor[l].
+    Returns one channel permutation per tensor."""
+    n = len(layers)
+    descs = (LayerDesc * n)()
+    keep = []
+    chans = [0] * n_tensors
+    for i, l in enumerate(layers):
+        d, k = _desc(l["kind"], l["w"], l["go"], l["gi"])
+        descs[i] = d
+        keep.append(k)
+        if 0 <= in_tensor[i] < n_tensors:
+            chans[in_tensor[i]] = d.c_in
+        if 0 <= out_tensor[i] < n_tensors:
+            chans[out_tensor[i]] = d.c_out
+    perms = [np.empty(max(c, 1), dtype=np.int32) for c in chans]
+    pp = (C.c_void_p * n_tensors)(*[p.ctypes.data for p in perms])
+    fixed = None if tensor_fixed is None else (C.c_int * n_tensors)(*tensor_fixed)
+    _check(_lib.lib().sbn_rearrange_graph(descs, n, (C.c_int * n)(*in_tensor), (C.c_int * n)(*out_tensor), n_tensors,
+                                          fixed, sparsity_percent, seed, max_iters, pp))
     return perms
 
 

@@ -105,34 +105,43 @@ static void permute_ohwi(const float* w, int c_out, int taps, int c_in, const in
 }
 
 // ---------------------------------------------------------------------------
-// Rearrangement search (Section 3.4).  Works on per-filter column-group norms
-// a[f][j] = l1 norm of filter f over channel group j (all taps); the norm of a
-// block is the sum of a[f][j] over the go filters of its row group.
+// Rearrangement search (Section 3.4).  A tensor's channel order is the filter
+// order of every layer that produces it, so the search runs over one
+// permutation shared by all of them (PARTS): part k works on per-filter
+// column-group norms a_k[f][j] = l1 norm of filter f of layer k over its channel
+// group j (all taps); the norm of a block is the sum of a_k[f][j] over the go
+// filters of its row group; the objective is the sum over the parts of the
+// importance that survives pruning.
 // ---------------------------------------------------------------------------
 struct RowSearch {
-    int n = 0, go = 0, cols = 0, rows = 0;
-    size_t keep = 0;                       // number of blocks that survive pruning
-    std::vector<double> a;                 // [n][cols]
+    struct Part {
+        int cols = 0;
+        size_t keep = 0;                   // number of blocks that survive pruning
+        std::vector<double> a;             // [n][cols]
+        std::vector<double> s;             // block norms of the current order [rows][cols]
+    };
+    int n = 0, go = 0, rows = 0;
+    std::vector<Part> parts;
     std::vector<int32_t> perm;             // current order, rows*go
-    std::vector<double> s;                 // block norms of the current order [rows][cols]
     std::vector<double> tmp;
 
-    void row_norms(int row, const int32_t* members, double* out) const
+    static void row_norms(const Part& p, int go, const int32_t* members, double* out)
     {
-        (void)row;
-        for (int j = 0; j < cols; ++j) {
+        for (int j = 0; j < p.cols; ++j) {
             double v = 0.0;
-            for (int o = 0; o < go; ++o) v += a[(size_t)members[o] * cols + j];
+            for (int o = 0; o < go; ++o) v += p.a[(size_t)members[o] * p.cols + j];
             out[j] = v;
         }
     }
     void rebuild()
     {
-        s.resize((size_t)rows * cols);
-        for (int i = 0; i < rows; ++i) row_norms(i, &perm[(size_t)i * go], &s[(size_t)i * cols]);
+        for (Part& p : parts) {
+            p.s.resize((size_t)rows * p.cols);
+            for (int i = 0; i < rows; ++i) row_norms(p, go, &perm[(size_t)i * go], &p.s[(size_t)i * p.cols]);
+        }
     }
     // sum of the `keep` largest entries of v (v is reordered)
-    double top_sum(std::vector<double>& v) const
+    static double top_sum(std::vector<double>& v, size_t keep)
     {
         if (keep == 0) return 0.0;
         if (keep < v.size()) std::nth_element(v.begin(), v.begin() + (v.size() - keep), v.end());
@@ -142,8 +151,36 @@ struct RowSearch {
     }
     double objective()
     {
-        tmp = s;
-        return top_sum(tmp);
+        double t = 0.0;
+        for (Part& p : parts) {
+            tmp = p.s;
+            t += top_sum(tmp, p.keep);
+        }
+        return t;
+    }
+    // objective with rows ga and gb replaced by the norms of the current perm's members
+    double objective_with(int ga, int gb, std::vector<std::vector<double>>& ra, std::vector<std::vector<double>>& rb)
+    {
+        double t = 0.0;
+        for (size_t k = 0; k < parts.size(); ++k) {
+            Part& p = parts[k];
+            ra[k].resize((size_t)p.cols);
+            rb[k].resize((size_t)p.cols);
+            row_norms(p, go, &perm[(size_t)ga * go], ra[k].data());
+            row_norms(p, go, &perm[(size_t)gb * go], rb[k].data());
+            tmp = p.s;
+            std::copy(ra[k].begin(), ra[k].end(), tmp.begin() + (size_t)ga * p.cols);
+            std::copy(rb[k].begin(), rb[k].end(), tmp.begin() + (size_t)gb * p.cols);
+            t += top_sum(tmp, p.keep);
+        }
+        return t;
+    }
+    void commit(int ga, int gb, const std::vector<std::vector<double>>& ra, const std::vector<std::vector<double>>& rb)
+    {
+        for (size_t k = 0; k < parts.size(); ++k) {
+            std::copy(ra[k].begin(), ra[k].end(), parts[k].s.begin() + (size_t)ga * parts[k].cols);
+            std::copy(rb[k].begin(), rb[k].end(), parts[k].s.begin() + (size_t)gb * parts[k].cols);
+        }
     }
 };
 
@@ -165,6 +202,20 @@ static void canonicalize(std::vector<int32_t>& perm, int go)
     }
     std::sort(g.begin(), g.end(), [](const std::vector<int32_t>& x, const std::vector<int32_t>& y) { return x[0] < y[0]; });
     for (int i = 0; i < rows; ++i) std::copy(g[(size_t)i].begin(), g[(size_t)i].end(), perm.begin() + (size_t)i * go);
+}
+
+// Number of canonical groupings of n filters into groups of go, n! / ((go!)^(n/go) (n/go)!)
+// (Section 3.4's canonical form), saturating at `cap`.
+static double canonical_count(int n, int go, double cap)
+{
+    double c = 1.0;
+    for (int left = n; left > 0; left -= go) {          // the first free filter opens a group: C(left-1, go-1) ways
+        double ways = 1.0;
+        for (int i = 1; i < go; ++i) ways = ways * (double)(left - i) / (double)i;
+        c *= ways;
+        if (c > cap) return cap;
+    }
+    return c;
 }
 
 // Enumerates every canonical grouping (first free filter opens a group, the
@@ -189,7 +240,6 @@ static void exhaustive(RowSearch& rs, std::vector<int32_t>& cur, std::vector<cha
     used[(size_t)first] = 1;
     cur[(size_t)filled] = first;
     // choose go-1 more members > first, ascending
-    std::vector<int> pick((size_t)go - 1);
     std::vector<int> cand;
     for (int f = first + 1; f < n; ++f)
         if (!used[(size_t)f]) cand.push_back(f);
@@ -216,26 +266,49 @@ static void exhaustive(RowSearch& rs, std::vector<int32_t>& cur, std::vector<cha
     used[(size_t)first] = 0;
 }
 
-static void search_rows(const float* wc, int c_out, int taps, int c_in, int go, int gi, int pct, uint64_t seed,
-                        int max_iters, std::vector<int32_t>& perm_out)
+// Layers at most this many canonical groupings large are searched exhaustively (12 filters in
+// groups of 4: 5 775; 16 in groups of 8: 6 435; 8 in groups of 4: 35).
+#ifndef SBN_EXHAUSTIVE_LIMIT
+#define SBN_EXHAUSTIVE_LIMIT 20000.0       // (a build with 0 runs the bounded search everywhere: used to compare the two)
+#endif
+constexpr double kExhaustiveLimit = SBN_EXHAUSTIVE_LIMIT;
+
+struct SearchPart {
+    const float* wc;                       // OHWI weights, channels already in their final order
+    int taps, c_in, gi;
+};
+
+// One tensor's filter order from the layers that produce it.  Small cases: every canonical
+// grouping.  Otherwise a seeded, bounded local search over swaps of two filters of different
+// groups ("bounded regression" in the paper's words; its algorithm is not given): a swap is kept
+// if the objective strictly increases; after a run of rejected candidates as long as the number
+// of filters the search restarts from the best order so far with two random swaps applied, and
+// the best order ever seen is returned -- never worse than the identity it starts from.
+static void search_rows(const std::vector<SearchPart>& parts, int c_out, int go, int pct, uint64_t seed, int max_iters,
+                        std::vector<int32_t>& perm_out)
 {
     RowSearch rs;
     rs.n = c_out;
     rs.go = go;
-    rs.cols = c_in / gi;
     rs.rows = c_out / go;
-    const size_t nb = (size_t)rs.rows * rs.cols;
-    rs.keep = nb - removed_count(nb, pct);
-    rs.a.assign((size_t)c_out * rs.cols, 0.0);
-    for (int f = 0; f < c_out; ++f)
-        for (int t = 0; t < taps; ++t) {
-            const float* q = wc + ((size_t)f * taps + t) * c_in;
-            for (int c = 0; c < c_in; ++c) rs.a[(size_t)f * rs.cols + c / gi] += std::fabs((double)q[c]);
-        }
+    for (const SearchPart& sp : parts) {
+        RowSearch::Part p;
+        p.cols = sp.c_in / sp.gi;
+        const size_t nb = (size_t)rs.rows * p.cols;
+        p.keep = nb - removed_count(nb, pct);
+        p.a.assign((size_t)c_out * p.cols, 0.0);
+        for (int f = 0; f < c_out; ++f)
+            for (int t = 0; t < sp.taps; ++t) {
+                const float* q = sp.wc + ((size_t)f * sp.taps + t) * sp.c_in;
+                for (int c = 0; c < sp.c_in; ++c) p.a[(size_t)f * p.cols + c / sp.gi] += std::fabs((double)q[c]);
+            }
+        rs.parts.push_back(std::move(p));
+    }
     perm_out.resize((size_t)c_out);
     std::iota(perm_out.begin(), perm_out.end(), 0);
+    if (rs.rows < 2 || rs.parts.empty()) return;
 
-    if (c_out <= 8) {
+    if (canonical_count(c_out, go, kExhaustiveLimit + 1) <= kExhaustiveLimit) {
         std::vector<int32_t> cur((size_t)c_out), best = perm_out;
         std::vector<char> used((size_t)c_out, 0);
         double best_obj = -1.0;
@@ -246,36 +319,50 @@ static void search_rows(const float* wc, int c_out, int taps, int c_in, int go, 
 
     rs.perm = perm_out;
     rs.rebuild();
-    double cur_obj = rs.objective();
-    if (rs.rows < 2) return;
+    double cur_obj = rs.objective(), best_obj = cur_obj;
+    std::vector<int32_t> best = rs.perm;
     uint64_t st = seed;
-    std::vector<double> ra((size_t)rs.cols), rb((size_t)rs.cols);
-    for (int it = 0; it < max_iters; ++it) {
+    std::vector<std::vector<double>> ra(rs.parts.size()), rb(rs.parts.size());
+    int rejected = 0;
+    auto random_pair = [&](int& pa, int& pb) {
         const uint64_t r0 = splitmix64(st), r1 = splitmix64(st);
-        const int pa = (int)(r0 % (uint64_t)c_out);
-        int pb = (int)(r1 % (uint64_t)c_out);
-        const int ga = pa / go;
-        int gb = pb / go;
-        if (ga == gb) {                                   // force a different group, deterministically
-            gb = (gb + 1 + (int)((r1 >> 32) % (uint64_t)(rs.rows - 1))) % rs.rows;
+        pa = (int)(r0 % (uint64_t)c_out);
+        pb = (int)(r1 % (uint64_t)c_out);
+        if (pa / go == pb / go) {                             // force a different group, deterministically
+            const int gb = (pb / go + 1 + (int)((r1 >> 32) % (uint64_t)(rs.rows - 1))) % rs.rows;
             pb = gb * go + pb % go;
         }
+    };
+    for (int it = 0; it < max_iters; ++it) {
+        if (rejected >= c_out) {                              // stuck: restart near the best order so far
+            rs.perm = best;
+            for (int k = 0; k < 2; ++k) {
+                int pa, pb;
+                random_pair(pa, pb);
+                std::swap(rs.perm[(size_t)pa], rs.perm[(size_t)pb]);
+            }
+            rs.rebuild();
+            cur_obj = rs.objective();
+            rejected = 0;
+            if (cur_obj > best_obj) best_obj = cur_obj, best = rs.perm;
+            continue;
+        }
+        int pa, pb;
+        random_pair(pa, pb);
+        const int ga = pa / go, gb = pb / go;
         std::swap(rs.perm[(size_t)pa], rs.perm[(size_t)pb]);
-        rs.row_norms(ga, &rs.perm[(size_t)ga * go], ra.data());
-        rs.row_norms(gb, &rs.perm[(size_t)gb * go], rb.data());
-        rs.tmp = rs.s;
-        std::copy(ra.begin(), ra.end(), rs.tmp.begin() + (size_t)ga * rs.cols);
-        std::copy(rb.begin(), rb.end(), rs.tmp.begin() + (size_t)gb * rs.cols);
-        const double obj = rs.top_sum(rs.tmp);
+        const double obj = rs.objective_with(ga, gb, ra, rb);
         if (obj > cur_obj) {
             cur_obj = obj;
-            std::copy(ra.begin(), ra.end(), rs.s.begin() + (size_t)ga * rs.cols);
-            std::copy(rb.begin(), rb.end(), rs.s.begin() + (size_t)gb * rs.cols);
+            rs.commit(ga, gb, ra, rb);
+            rejected = 0;
+            if (cur_obj > best_obj) best_obj = cur_obj, best = rs.perm;
         } else {
             std::swap(rs.perm[(size_t)pa], rs.perm[(size_t)pb]);
+            ++rejected;
         }
     }
-    perm_out = rs.perm;
+    perm_out = best;
     canonicalize(perm_out, go);
 }
 
@@ -508,39 +595,110 @@ int sbn_conv3x3_pattern_apply(const float* w, int c_out, int c_in, int share, co
     return SBN_OK;
 }
 
+// Tensors in increasing number; a tensor's order is searched over all layers that write it, each
+// with its channels in the order of its input tensor if that is already decided (lower number),
+// else in original order.
+static int sbn_rearrange_graph_impl(const sbn_layer_desc_t* layers, int n_layers, const int* in_tensor,
+                                    const int* out_tensor, int n_tensors, const int* tensor_fixed, int pct,
+                                    uint64_t seed, int max_iters, int32_t* const* perm_out)
+{
+    clear_error();
+    if (!layers || !in_tensor || !out_tensor || !perm_out || n_layers < 0 || n_tensors <= 0)
+        return fail(SBN_EINVAL, "sbn_rearrange_graph: NULL pointer or empty graph");
+    if (pct < 0 || pct > 100) return fail(SBN_EINVAL, "sparsity_percent must be in [0,100] (got %d)", pct);
+    if (max_iters < 0) return fail(SBN_EINVAL, "max_iters must be >= 0");
+    std::vector<int> channels((size_t)n_tensors, 0);          // channel count of every tensor, 0 = not seen yet
+    auto see = [&](int t, int c, int l, const char* side) -> int {
+        if (t < 0 || t >= n_tensors) return fail(SBN_EINVAL, "layer %d: %s tensor %d is not in 0..%d", l, side, t, n_tensors - 1);
+        if (channels[(size_t)t] && channels[(size_t)t] != c)
+            return fail(SBN_ESHAPE, "tensor %d has %d channels but layer %d %s %d", t, channels[(size_t)t], l,
+                        side[0] == 'i' ? "reads" : "writes", c);
+        channels[(size_t)t] = c;
+        return SBN_OK;
+    };
+    for (int l = 0; l < n_layers; ++l) {
+        const sbn_layer_desc_t& d = layers[l];
+        if (!d.w) return fail(SBN_EINVAL, "sbn_rearrange_graph: layer %d has no weights", l);
+        if (int rc = check_geometry(d.kind, d.c_in, d.c_out, d.go, d.gi)) return rc;
+        if (int rc = see(in_tensor[l], d.c_in, l, "input")) return rc;
+        if (int rc = see(out_tensor[l], d.c_out, l, "output")) return rc;
+    }
+    for (int t = 0; t < n_tensors; ++t) {
+        if (!channels[(size_t)t]) return fail(SBN_EINVAL, "tensor %d is used by no layer", t);
+        if (!perm_out[t]) return fail(SBN_EINVAL, "sbn_rearrange_graph: no room for the order of tensor %d", t);
+    }
+    std::vector<char> decided((size_t)n_tensors, 0);
+    std::vector<std::vector<float>> wc;
+    std::vector<int32_t> perm;
+    for (int t = 0; t < n_tensors; ++t) {
+        const int c = channels[(size_t)t];
+        std::vector<SearchPart> parts;
+        wc.clear();
+        int go = 0;
+        if (!(tensor_fixed && tensor_fixed[t])) {
+            for (int l = 0; l < n_layers; ++l) {
+                if (out_tensor[l] != t) continue;
+                const sbn_layer_desc_t& d = layers[l];
+                if (go && d.go != go)
+                    return fail(SBN_ESHAPE, "the layers that write tensor %d group their filters by %d and by %d", t, go, d.go);
+                go = d.go;
+                const int taps = d.kind == SBN_CONV3X3 ? 9 : 1;
+                const int32_t* pin = decided[(size_t)in_tensor[l]] ? perm_out[in_tensor[l]] : nullptr;
+                wc.emplace_back();
+                permute_ohwi(d.w, d.c_out, taps, d.c_in, nullptr, pin, wc.back());
+                for (float v : wc.back())
+                    if (!std::isfinite(v)) return fail(SBN_EINVAL, "sbn_rearrange_graph: the weights of layer %d contain NaN or infinity", l);
+                parts.push_back(SearchPart{nullptr, taps, d.c_in, d.gi});
+            }
+            for (size_t k = 0; k < parts.size(); ++k) parts[k].wc = wc[k].data();
+        }
+        if (parts.empty()) {                                 // a network input, or kept in place: identity
+            for (int i = 0; i < c; ++i) perm_out[t][i] = i;
+        } else {
+            const uint64_t s = seed ^ (0xD1B54A32D192ED03ull * (uint64_t)(t + 1));
+            search_rows(parts, c, go, pct, s, max_iters, perm);
+            std::copy(perm.begin(), perm.end(), perm_out[t]);
+        }
+        decided[(size_t)t] = 1;
+    }
+    return SBN_OK;
+}
+
+// The chain / tree form: tensor 0 is the network input, tensor l + 1 the output of layer l.
 static int sbn_rearrange_impl(const sbn_layer_desc_t* layers, int n_layers, const int* parent, const int* keep_output_order,
-                  int pct, uint64_t seed, int max_iters, int32_t* const* perm_out)
+                              int pct, uint64_t seed, int max_iters, int32_t* const* perm_out)
 {
     clear_error();
     if (!layers || !parent || !perm_out || n_layers < 0) return fail(SBN_EINVAL, "sbn_rearrange: NULL pointer");
-    if (pct < 0 || pct > 100) return fail(SBN_EINVAL, "sparsity_percent must be in [0,100] (got %d)", pct);
-    if (max_iters < 0) return fail(SBN_EINVAL, "max_iters must be >= 0");
     for (int l = 0; l < n_layers; ++l) {
-        const sbn_layer_desc_t& d = layers[l];
-        if (!d.w || !perm_out[l]) return fail(SBN_EINVAL, "sbn_rearrange: layer %d has a NULL pointer", l);
-        if (int rc = check_geometry(d.kind, d.c_in, d.c_out, d.go, d.gi)) return rc;
+        if (!perm_out[l]) return fail(SBN_EINVAL, "sbn_rearrange: layer %d has a NULL pointer", l);
         if (parent[l] >= l || parent[l] < -1)
             return fail(SBN_ESHAPE, "parent[%d] = %d: parents must come first", l, parent[l]);
-        if (parent[l] >= 0 && layers[parent[l]].c_out != d.c_in)
-            return fail(SBN_ESHAPE, "layer %d reads %d channels but its parent %d writes %d", l, d.c_in, parent[l],
+        if (parent[l] >= 0 && layers[parent[l]].c_out != layers[l].c_in)
+            return fail(SBN_ESHAPE, "layer %d reads %d channels but its parent %d writes %d", l, layers[l].c_in, parent[l],
                         layers[parent[l]].c_out);
     }
-    std::vector<float> wc;
-    std::vector<int32_t> perm;
+    // Layers that read the network input directly may differ in c_in: each gets an input tensor of its own.
+    std::vector<int> in_t((size_t)n_layers), out_t((size_t)n_layers), fixed;
+    int n_tensors = n_layers;
     for (int l = 0; l < n_layers; ++l) {
-        const sbn_layer_desc_t& d = layers[l];
-        const int taps = d.kind == SBN_CONV3X3 ? 9 : 1;
-        if (keep_output_order && keep_output_order[l]) {
-            for (int i = 0; i < d.c_out; ++i) perm_out[l][i] = i;
-            continue;
-        }
-        const int32_t* pin = parent[l] >= 0 ? perm_out[parent[l]] : nullptr;
-        permute_ohwi(d.w, d.c_out, taps, d.c_in, nullptr, pin, wc);
-        uint64_t s = seed ^ (0xD1B54A32D192ED03ull * (uint64_t)(l + 1));
-        search_rows(wc.data(), d.c_out, taps, d.c_in, d.go, d.gi, pct, s, max_iters, perm);
-        std::copy(perm.begin(), perm.end(), perm_out[l]);
+        out_t[(size_t)l] = l;
+        in_t[(size_t)l] = parent[l] >= 0 ? parent[l] : n_tensors++;
     }
-    return SBN_OK;
+    fixed.assign((size_t)n_tensors, 0);
+    for (int l = 0; l < n_layers; ++l) fixed[(size_t)l] = keep_output_order && keep_output_order[l] ? 1 : 0;
+    for (int t = n_layers; t < n_tensors; ++t) fixed[(size_t)t] = 1;
+    // The graph call decides tensors in increasing number and looks an input's order up only if
+    // it is decided: network inputs (numbered last) count as identity either way.
+    std::vector<std::vector<int32_t>> extra((size_t)(n_tensors - n_layers));
+    std::vector<int32_t*> ptrs((size_t)n_tensors);
+    for (int l = 0; l < n_layers; ++l) ptrs[(size_t)l] = perm_out[l];
+    for (int t = n_layers; t < n_tensors; ++t) {
+        extra[(size_t)(t - n_layers)].resize((size_t)layers[std::find(in_t.begin(), in_t.end(), t) - in_t.begin()].c_in);
+        ptrs[(size_t)t] = extra[(size_t)(t - n_layers)].data();
+    }
+    return sbn_rearrange_graph_impl(layers, n_layers, in_t.data(), out_t.data(), n_tensors, fixed.data(), pct, seed, max_iters,
+                                    ptrs.data());
 }
 
 static int sbn_pack_impl(const sbn_layer_desc_t* d, int device, sbn_packed_t** out)
@@ -728,6 +886,16 @@ int sbn_rearrange(const sbn_layer_desc_t* layers, int n_layers, const int* paren
 int sbn_pack(const sbn_layer_desc_t* d, int device, sbn_packed_t** out)
 {
     return guarded("sbn_pack", [&]() -> int { return sbn_pack_impl(d, device, out); });
+}
+
+int sbn_rearrange_graph(const sbn_layer_desc_t* layers, int n_layers, const int* in_tensor, const int* out_tensor,
+                        int n_tensors, const int* tensor_fixed, int pct, uint64_t seed, int max_iters,
+                        int32_t* const* perm_per_tensor_out)
+{
+    return guarded("sbn_rearrange_graph", [&]() -> int {
+        return sbn_rearrange_graph_impl(layers, n_layers, in_tensor, out_tensor, n_tensors, tensor_fixed, pct, seed,
+                                        max_iters, perm_per_tensor_out);
+    });
 }
 
 }  // extern "C"

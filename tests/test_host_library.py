@@ -176,6 +176,68 @@ def test_rearrange_exhaustive_equals_brute_force_optimum():
         assert math.isclose(R.retained_l1(w[perm], go, gi, 50), obj, rel_tol=1e-12)
 
 
+def test_rearrange_exhaustive_reaches_to_twelve_filters():
+    """12 filters in groups of 4 (5 775 canonical groupings) and 16 in groups of 8 (6 435) are
+    still enumerated: the result is the oracle's brute-force optimum."""
+    for seed, n, go, pct in ((353, 12, 4, 30), (354, 12, 4, 70), (355, 16, 8, 50)):
+        w = W.he_weights(seed, n, 1, 1, 16)
+        perm = S.sbn_rearrange([dict(kind=S.SBN_CONV1X1, w=w, go=go, gi=4)], [-1], pct)[0]
+        best, obj = R.best_row_grouping(w, go, 4, pct)
+        assert np.array_equal(perm, best)
+        assert math.isclose(R.retained_l1(w[perm], go, 4, pct), obj, rel_tol=1e-12)
+
+
+def _tiny_residual_graph(seed):
+    """x (8 ch) -> conv_a -> u (8 ch) -> conv_b -> y (8 ch), out = y + x: the skip connection makes
+    tensor y carry the order of tensor x, i.e. conv_b writes the tensor conv_a reads."""
+    wa, wb = W.he_weights(seed, 8, 1, 1, 8), W.he_weights(seed + 1, 8, 1, 1, 8)
+    layers = [dict(kind=S.SBN_CONV1X1, w=wa, go=4, gi=4), dict(kind=S.SBN_CONV1X1, w=wb, go=4, gi=4)]
+    return layers, [0, 1], [1, 0]             # tensor 0 = x = y's order class, tensor 1 = u
+
+
+def test_rearrange_graph_residual_block_keeps_the_function_and_finds_the_joint_optimum():
+    layers, tin, tout = _tiny_residual_graph(371)
+    perms = S.sbn_rearrange_graph(layers, tin, tout, 2, 50, seed=3, max_iters=200)
+    p0, p1 = perms
+    assert R.is_permutation(p0, 8) and R.is_permutation(p1, 8)
+    # tensor 0 is decided first: its only writer conv_b still has its channels in original order
+    # then; 8 filters are enumerated, so the result is the brute-force optimum of that problem
+    best0, _ = R.best_row_grouping(layers[1]["w"], 4, 4, 50)
+    assert np.array_equal(p0, best0)
+    # tensor 1: its writer conv_a reads tensor 0, already decided
+    wa_cols = R.permute_weights(layers[0]["w"], None, p0)
+    best1, _ = R.best_row_grouping(wa_cols, 4, 4, 50)
+    assert np.array_equal(p1, best1)
+    # the block's function: out = conv_b(conv_a(x)) + x, evaluated in permuted channel space
+    x = W.uniform_activation(372, (1, 3, 3, 8))
+    u, _ = R.conv_nhwc(x, layers[0]["w"])
+    y, _ = R.conv_nhwc(u, layers[1]["w"])
+    ref = y.astype(np.float64) + x
+    xp = x[..., p0]
+    up, _ = R.conv_nhwc(xp, R.permute_weights(layers[0]["w"], p1, p0))
+    yp, _ = R.conv_nhwc(up, R.permute_weights(layers[1]["w"], p0, p1))
+    got = yp.astype(np.float64) + xp
+    np.testing.assert_allclose(got, ref[..., p0], rtol=0, atol=1e-5)
+
+
+def test_rearrange_graph_two_writers_share_one_order_maximising_the_sum():
+    """Two branches summed into one tensor: one filter order for both, the one with the largest
+    sum of retained importances (brute force over the 35 canonical groupings of 8 filters)."""
+    w1, w2 = W.he_weights(381, 8, 1, 1, 8), W.he_weights(382, 8, 1, 1, 16)
+    layers = [dict(kind=S.SBN_CONV1X1, w=w1, go=4, gi=4), dict(kind=S.SBN_CONV1X1, w=w2, go=4, gi=4)]
+    perms = S.sbn_rearrange_graph(layers, [0, 1], [2, 2], 3, 50)
+    assert np.array_equal(perms[0], np.arange(8)) and np.array_equal(perms[1], np.arange(16))   # network inputs
+    best, best_obj = None, -1.0
+    for g in R.canonical_groupings(8, 4):
+        obj = R.retained_l1(w1[list(g)], 4, 4, 50) + R.retained_l1(w2[list(g)], 4, 4, 50)
+        if obj > best_obj:
+            best, best_obj = g, obj
+    assert np.array_equal(perms[2], np.asarray(best, dtype=np.int32))
+    with pytest.raises(S.SbnError):            # writers that disagree on the channel count
+        S.sbn_rearrange_graph([layers[0], dict(kind=S.SBN_CONV1X1, w=W.he_weights(383, 16, 1, 1, 16), go=4, gi=4)],
+                              [0, 1], [2, 2], 3, 50)
+
+
 def test_rearrange_finds_planted_grouping():
     """Strong and weak filters interleaved: like must be grouped with like."""
     rng = np.random.default_rng(361)

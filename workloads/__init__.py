@@ -114,6 +114,20 @@ def he_weights(seed: int, c_out: int, kh: int, kw: int, c_in: int) -> np.ndarray
     return normal_weights(seed, (c_out, kh, kw, c_in), float(np.sqrt(2.0 / (kh * kw * c_in))))
 
 
+def planted_weights(seed: int, c_out: int, c_in: int, n_profiles: int = 4, weak: float = 0.15) -> np.ndarray:
+    """1x1 weights with structure for the rearrangement to find (trained networks have filters
+    that attend to the same input channels; i.i.d. weights have none): filter f belongs to one of
+    n_profiles profiles, drawn by a seeded shuffle so that neighbouring filters differ, and is
+    He-normal on the 4-channel groups j with j % n_profiles == profile, `weak` times that
+    elsewhere.  Input generator only: which grouping is best is for the search to find."""
+    rng = np.random.default_rng(seed)
+    w = rng.standard_normal((c_out, 1, 1, c_in)) * np.sqrt(2.0 / c_in)
+    profile = rng.permutation(c_out) % n_profiles
+    group_of_channel = (np.arange(c_in) // 4) % n_profiles
+    scale = np.where(profile[:, None] == group_of_channel[None, :], 1.0, weak)
+    return (w * scale[:, None, None, :]).astype(np.float32)
+
+
 def small_bias(seed: int, n: int) -> np.ndarray:
     """fp32 bias ~ N(0, 0.01^2)."""
     rng = np.random.default_rng(seed)
