@@ -53,6 +53,9 @@ def parse():
     ap.add_argument("--no-fuse", action="store_true",
                     help="mobilenet: run every depthwise layer as its own launch (default: the first three run "
                          "inside the 1x1 layers that consume them)")
+    ap.add_argument("--multi-layer", action="store_true",
+                    help="mobilenet: runs of small items (few pixels) leave as one launch with grid-wide barriers "
+                         "(slower than one launch per item on this machine; kept as a measurement)")
     ap.add_argument("--dw-pattern", action="store_true",
                     help="mobilenet workload: 3:9 pattern-prune the depthwise layers (groups of 16 channels)")
     return ap.parse_args()
@@ -301,6 +304,8 @@ def run_mobilenet(a, torch, S, W):
     pack_ms = (time.perf_counter() - t0) * 1e3
     if a.no_fuse:
         S.sbn_chain_set_fusion(chain, False)
+    if a.multi_layer:
+        S.sbn_chain_set_multi_layer(chain, True)
     hw = W.STEM["hw_in"]
     g = torch.Generator(device="cuda").manual_seed(4000)
     x = torch.rand((B, hw, hw, 3), device="cuda", generator=g) * 2 - 1

@@ -387,6 +387,30 @@ int sbn_pointwise_chain_static(const sbn_chain_t* c, const float* x, float* y, i
  */
 int sbn_chain_set_fusion(sbn_chain_t* c, int enable);
 
+/*
+ * Inputs of few pixels (batch 1 of the deep layers: the paper's own setting is
+ * single-image latency, Section 4.3).  Off by default, enable = 1 switches it
+ * on for the chain: runs of at least three consecutive depthwise / 1x1 items
+ * with at most 1024 output pixels each (1x1 layers: input channels a multiple
+ * of 4 and at least 128) are queued as ONE launch: a grid of resident
+ * workgroups walks the items as phases with a grid-wide barrier in between.
+ * On MI355X this is SLOWER than one launch per item (whole MobileNet-v1 on one
+ * image: 0.36 ms against 0.15 ms): a grid-wide barrier has to write one XCD's
+ * L2 back and invalidate the others', about 14 us, where the boundary between
+ * two launches costs about 6 us.  The path is kept for callers that must bound
+ * the number of launches.  Results agree with the separate launches up to fp32
+ * summation order.  The barrier's state lives in the chain: two runs of the
+ * SAME chain must not overlap in time when they use this path (one stream, or
+ * events between them).  Waits at the barrier are bounded; a launch that runs
+ * into the bound ends early, later multi-layer launches of the chain return at
+ * once (their outputs are not written), and sbn_chain_check reports it: call it
+ * after synchronising when this path is on.
+ * sbn_chain_check: synchronous (copies three words back): SBN_OK, or SBN_EHIP
+ * if a multi-layer launch of the chain ever gave up.
+ */
+int sbn_chain_set_multi_layer(sbn_chain_t* c, int enable);
+int sbn_chain_check(const sbn_chain_t* c);
+
 void sbn_chain_free(sbn_chain_t* c);
 
 /* ------------------------------------------------------------------ measurement helpers */

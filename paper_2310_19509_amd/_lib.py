@@ -82,6 +82,8 @@ SYMBOLS = {
                                       C.c_size_t, C.POINTER(C.c_void_p), C.c_void_p]),
     "sbn_pointwise_chain_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                                              C.POINTER(C.c_void_p), C.c_void_p]),
+    "sbn_chain_set_multi_layer": (C.c_int, [C.c_void_p, C.c_int]),
+    "sbn_chain_check": (C.c_int, [C.c_void_p]),
     "sbn_chain_free": (None, [C.c_void_p]),
     "sbn_packed_work": (C.c_int, [C.c_void_p, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
     "sbn_copy_bytes": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),

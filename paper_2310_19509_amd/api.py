@@ -18,7 +18,7 @@ __all__ = [
     "SBN_STATIC_WORKSPACE_BYTES", "sbn_chain_free",
     "sbn_copy_bytes", "sbn_roof_mfma", "sbn_roof_lds", "sbn_roof_read", "dw_item", "sparse_item", "avgpool_item", "stem_item", "SBN_ITEM_STEM3X3",
     "SBN_DW_PATTERN_DENSE", "sbn_dw_pattern_groups", "sbn_dw_pattern_select", "sbn_dw_pattern_apply",
-    "sbn_force_kernel_form", "sbn_chain_set_fusion", "SBN_K3_PATTERNS", "SBN_K3_PATTERN_DENSE", "sbn_conv3x3_pattern_taps", "sbn_conv3x3_pattern_select",
+    "sbn_force_kernel_form", "sbn_chain_set_fusion", "sbn_chain_set_multi_layer", "sbn_chain_check", "SBN_K3_PATTERNS", "SBN_K3_PATTERN_DENSE", "sbn_conv3x3_pattern_taps", "sbn_conv3x3_pattern_select",
     "sbn_conv3x3_pattern_apply",
 ]
 
@@ -446,6 +446,16 @@ def sbn_pointwise_chain_static(c: Chain, x, y, n: int, h: int, w: int, layer_out
             raise ValueError(f"layer_outputs has {len(layer_outputs)} entries, the chain has {c.n_items} items")
         lo = (C.c_void_p * len(layer_outputs))(*[_dev_ptr(t) for t in layer_outputs])
     _check(_lib.lib().sbn_pointwise_chain_static(c.handle, _dev_ptr(x), _dev_ptr(y), n, h, w, lo, _stream(stream)))
+
+
+def sbn_chain_set_multi_layer(c: Chain, enable: bool) -> None:
+    """Switch the one-launch path for runs of small items on (default) or off."""
+    _check(_lib.lib().sbn_chain_set_multi_layer(c.handle, 1 if enable else 0))
+
+
+def sbn_chain_check(c: Chain) -> None:
+    """Raises if a multi-layer launch of the chain gave up at a grid barrier (synchronous)."""
+    _check(_lib.lib().sbn_chain_check(c.handle))
 
 
 def sbn_chain_free(c: Chain) -> None:

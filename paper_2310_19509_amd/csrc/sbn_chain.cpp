@@ -24,6 +24,9 @@ struct sbn_chain {
     int c_in = 0;
     void* d_blob = nullptr;
     bool fuse_dw = true;           // run a depthwise item and the small 1x1 layer after it as one launch
+    bool multi_layer = false;      // few pixels: consecutive depthwise / 1x1 items as phases of one launch (opt-in)
+    unsigned* d_sync = nullptr;    // its grid barrier's words (in d_blob)
+    int cus = 256;                 // compute units of the device
     ~sbn_chain()
     {
         if (d_blob) (void)hipFree(d_blob);
@@ -125,8 +128,70 @@ int run_chain(const sbn_chain* c, const float* x, float* y, int n, int h, int w,
     const float* src = x;
     Shape s{n, h, w, c->c_in};
     int which = 0;                   // half of the workspace the next launch writes
+    // Items that qualify as phases of a multi-layer launch: a depthwise layer, or a 1x1 layer
+    // whose input channels are a multiple of 4, with at most 1024 output pixels (every such launch
+    // would sit at the launch-latency floor).
+    auto tail_item = [&](const sbn_chain::Item& it, const Shape& in) {
+        const Shape o = next_shape(it, in);
+        if (o.n * o.h * o.w > 1024) return false;
+        if (it.item == SBN_ITEM_DW3X3) return true;
+        return it.item == SBN_ITEM_SPARSE && it.packed->kind == SBN_CONV1X1 && it.packed->c_in % 4 == 0 &&
+               it.packed->c_in >= 128;
+    };
     for (size_t i = 0; i < c->items.size(); ++i) {
         const sbn_chain::Item& it = c->items[i];
+        if (c->multi_layer && tail_item(it, s)) {
+            // the longest run of such items from here (each with its optional copy) that fits one launch
+            size_t j = i;
+            int phases = 0;
+            Shape sj = s;
+            while (j < c->items.size() && tail_item(c->items[j], sj)) {
+                const int need = 1 + (layer_outputs && layer_outputs[j] ? 1 : 0);
+                if (phases + need > kTailMaxPhases) break;
+                phases += need;
+                sj = next_shape(c->items[j], sj);
+                ++j;
+            }
+            if (j - i >= 3) {
+                TailArgs a;
+                a.n_phases = 0;
+                for (size_t k = i; k < j; ++k) {
+                    const sbn_chain::Item& ik = c->items[k];
+                    const Shape o = next_shape(ik, s);
+                    float* dst = k + 1 == c->items.size() ? y : buf[which];
+                    TailPhase& ph = a.ph[a.n_phases++];
+                    ph = TailPhase{};
+                    ph.src = src;
+                    ph.dst = dst;
+                    if (ik.item == SBN_ITEM_DW3X3) {
+                        ph.kind = 0;
+                        ph.n = (int)s.n, ph.h = s.h, ph.w = s.w, ph.c = s.c, ph.stride = ik.stride, ph.act = ik.act;
+                        ph.oh = o.h, ph.ow = o.w;
+                        ph.dw_w = ik.d_w, ph.dw_b = ik.d_b;
+                    } else {
+                        const sbn::DeviceLayout& L = ik.packed->dev;
+                        ph.kind = 1;
+                        ph.rec32 = L.d_records32, ph.woff32 = L.d_woff32, ph.wts = L.d_wts, ph.bias = L.d_bias;
+                        ph.K = ik.packed->c_in, ph.N = ik.packed->c_out, ph.n_bundles = L.n_bundles, ph.n_chunks32 = L.n_chunks32;
+                        ph.M = s.n * s.h * s.w;
+                        ph.act = ik.packed->act;
+                    }
+                    if (layer_outputs && layer_outputs[k]) {
+                        if (o.bytes() % 16) return fail(SBN_EINVAL, "output of item %zu is not a multiple of 16 bytes", k);
+                        TailPhase& cp = a.ph[a.n_phases++];
+                        cp = TailPhase{};
+                        cp.kind = 2;
+                        cp.src = dst, cp.dst = layer_outputs[k], cp.M = (long long)(o.bytes() / 16);
+                    }
+                    src = dst;
+                    s = o;
+                    which ^= 1;
+                }
+                if (int rc = launch_chain_tail(a, c->d_sync, c->cus, stream)) return rc;
+                i = j - 1;
+                continue;
+            }
+        }
         // A depthwise layer in front of a small 1x1 layer runs inside that layer's launch (its
         // output never exists in memory), unless the caller asked for a copy of it.
         if (c->fuse_dw && it.item == SBN_ITEM_DW3X3 && i + 1 < c->items.size() &&
@@ -201,7 +266,7 @@ static int chain_create_impl(const sbn_chain_item_t* items, int n_items, int dev
 
     std::vector<int32_t> order;      // order[ch] = original channel carried at position ch; empty = identity
     int cur_c = -1;
-    size_t dw_floats = 0;
+    size_t dw_floats = 64;           // the first 64 words stay zero: the multi-layer launch's barrier state
     for (int i = 0; i < n_items; ++i) {
         const sbn_chain_item_t& s = items[i];
         sbn_chain::Item it;
@@ -263,7 +328,7 @@ static int chain_create_impl(const sbn_chain_item_t* items, int n_items, int dev
         c->items.push_back(it);
     }
 
-    if (dw_floats) {
+    {
         int prev = 0;
         (void)hipGetDevice(&prev);
         hipError_t e = hipSetDevice(device);
@@ -275,8 +340,9 @@ static int chain_create_impl(const sbn_chain_item_t* items, int n_items, int dev
         }
         c->d_blob = blob;                      // owned by the chain from here on
         std::vector<float> host(dw_floats, 0.0f);
-        size_t off = 0;
+        size_t off = 64;
         std::vector<int32_t> ord;
+        c->d_sync = (unsigned*)blob;
         for (int i = 0; i < n_items; ++i) {
             sbn_chain::Item& it = c->items[(size_t)i];
             if (it.item == SBN_ITEM_SPARSE) ord = it.packed->perm_out;
@@ -332,6 +398,10 @@ static int chain_create_impl(const sbn_chain_item_t* items, int n_items, int dev
         (void)hipSetDevice(prev);
         if (rc) return rc;
     }
+    {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0) c->cus = cus;
+    }
     *out = holder.release();
     return SBN_OK;
 }
@@ -373,6 +443,26 @@ int sbn_chain_set_fusion(sbn_chain_t* c, int enable)
     clear_error();
     if (!c) return fail(SBN_EINVAL, "sbn_chain_set_fusion: chain is NULL");
     c->fuse_dw = enable != 0;
+    return SBN_OK;
+}
+
+int sbn_chain_set_multi_layer(sbn_chain_t* c, int enable)
+{
+    clear_error();
+    if (!c) return fail(SBN_EINVAL, "sbn_chain_set_multi_layer: chain is NULL");
+    c->multi_layer = enable != 0;
+    return SBN_OK;
+}
+
+int sbn_chain_check(const sbn_chain_t* c)
+{
+    clear_error();
+    if (!c) return fail(SBN_EINVAL, "sbn_chain_check: chain is NULL");
+    unsigned words[3] = {0, 0, 0};
+    hipError_t e = hipMemcpy(words, c->d_sync, sizeof words, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(SBN_EHIP, "sbn_chain_check: %s", hipGetErrorString(e));
+    if (words[2] != 0)
+        return fail(SBN_EHIP, "a multi-layer launch of this chain gave up waiting at a grid barrier; its outputs are not valid");
     return SBN_OK;
 }
 

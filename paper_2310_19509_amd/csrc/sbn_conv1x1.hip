@@ -25,6 +25,8 @@
 // tile is transposed through LDS and written as full rows of 16-byte stores.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "sbn_internal.h"
 
 namespace {
@@ -42,9 +44,12 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);   // raw, 32-bit words
 }
+// AUX = 16 (sc1): the access is coherent across the whole device -- it goes past the caches
+// that other XCDs do not see -- for data that workgroups hand to one another inside a launch.
+template <int AUX = 0>
 __device__ __forceinline__ v4f buf_load(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t scalar_off)
 {
-    return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)scalar_off, 0));
+    return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)scalar_off, AUX));
 }
 
 template <int ABID>
@@ -529,6 +534,109 @@ __global__ __launch_bounds__(256) void conv1x1_mixed_kernel(const float* __restr
     }
 }
 
+// ---- several chain items in one launch (few pixels) ---------------------------------------
+// Grid-wide barrier for a grid whose workgroups are all resident.  Sense reversal: the last
+// workgroup to arrive clears the arrival count and advances the generation the others wait
+// for, so the two words need no reset between barriers or launches.  Waits are bounded: after
+// spin_limit polls a workgroup sets the status word and the whole grid leaves (every wave
+// reaches an exit whatever happens to the others).  Returns false if the grid is to leave.
+__device__ __forceinline__ bool grid_barrier(unsigned* sync, unsigned n_wg, unsigned spin_limit, int* flag_lds)
+{
+    // The workgroup barrier orders every thread's stores before thread 0, whose device-scope
+    // release then writes this XCD's L2 back; after the wait its device-scope acquire drops the
+    // stale lines of this CU's vector cache and of the L2 before the second workgroup barrier
+    // lets the other threads read what the other workgroups wrote.
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int ok = 1;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        const unsigned gen = __hip_atomic_load(&sync[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned prev = __hip_atomic_fetch_add(&sync[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (prev + 1 == n_wg) {
+            __hip_atomic_store(&sync[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(&sync[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            unsigned spins = 0;
+            while (__hip_atomic_load(&sync[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen) {
+                __builtin_amdgcn_s_sleep(2);
+                if (++spins > spin_limit || __hip_atomic_load(&sync[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                    __hip_atomic_store(&sync[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ok = 0;
+                    break;
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        *flag_lds = ok;
+    }
+    __syncthreads();
+    return *flag_lds != 0;
+}
+
+// Dense depthwise 3x3 (+ bias, activation), pad 1, as a phase: a thread per four channels of
+// one output pixel, grid-stride.  w [9][c], b [c].
+__device__ __forceinline__ void tail_depthwise(const sbn::TailPhase& ph)
+{
+    const int c4n = ph.c >> 2;
+    const long long total = (long long)ph.n * ph.oh * ph.ow * c4n;
+    for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x) {
+        const int c4 = (int)(t % c4n) * 4;
+        long long pix = t / c4n;
+        const int ox = (int)(pix % ph.ow);
+        pix /= ph.ow;
+        const int oy = (int)(pix % ph.oh);
+        const long long b = pix / ph.oh;
+        v4f acc = *(const v4f*)(ph.dw_b + c4);
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) {
+            const int iy = oy * ph.stride + ky - 1;
+            if (iy < 0 || iy >= ph.h) continue;
+#pragma unroll
+            for (int kx = 0; kx < 3; ++kx) {
+                const int ix = ox * ph.stride + kx - 1;
+                if (ix < 0 || ix >= ph.w) continue;
+                acc += *(const v4f*)(ph.src + ((b * ph.h + iy) * ph.w + ix) * ph.c + c4) *
+                       *(const v4f*)(ph.dw_w + (ky * 3 + kx) * ph.c + c4);
+            }
+        }
+        if (ph.act == SBN_ACT_RELU) {
+            acc.x = fmaxf(acc.x, 0.f);
+            acc.y = fmaxf(acc.y, 0.f);
+            acc.z = fmaxf(acc.z, 0.f);
+            acc.w = fmaxf(acc.w, 0.f);
+        }
+        *(v4f*)(ph.dst + ((b * ph.oh + oy) * (long long)ph.ow + ox) * ph.c + c4) = acc;
+    }
+}
+
+constexpr int kTailWaves = 8;       // waves per workgroup: a 1x1 task is 64 pixels x one bundle, channels split eight ways
+
+__global__ __launch_bounds__(64 * kTailWaves) void chain_tail_kernel(sbn::TailArgs a, unsigned* sync, unsigned spin_limit)
+{
+    __shared__ __attribute__((aligned(16))) float pool[kTailWaves * 64 * 36];
+    __shared__ int flag;
+    if (__hip_atomic_load(&sync[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return;   // an earlier launch gave up
+    for (int p = 0; p < a.n_phases; ++p) {
+        const sbn::TailPhase& ph = a.ph[p];
+        if (ph.kind == 1) {
+            const long long n_tasks = ((ph.M + 63) / 64) * ph.n_bundles;
+            for (long long t = blockIdx.x; t < n_tasks; t += gridDim.x) {
+                splitk_tile<kTailWaves>(pool, ph.src, ph.dst, ph.rec32, ph.woff32, ph.wts, ph.bias, ph.M, ph.K, ph.N,
+                                        ph.n_chunks32, (t / ph.n_bundles) * 64, (int)(t % ph.n_bundles), ph.act);
+                __syncthreads();                       // the tile memory is free for the next task
+            }
+        } else if (ph.kind == 0) {
+            tail_depthwise(ph);
+        } else {
+            const v4f* s4 = (const v4f*)ph.src;
+            v4f* d4 = (v4f*)ph.dst;
+            for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < ph.M; i += (long long)gridDim.x * blockDim.x)
+                d4[i] = s4[i];
+        }
+        if (p + 1 < a.n_phases && !grid_barrier(sync, gridDim.x, spin_limit, &flag)) return;
+    }
+}
+
 template <int NW>
 int launch_splitk(const sbn_packed* p, const float* x, float* y, long long M, hipStream_t st)
 {
@@ -586,6 +694,30 @@ int launch_mixed(const sbn_packed* p, const float* x, float* y, long long M, lon
 }  // namespace
 
 namespace sbn {
+
+int launch_chain_tail(const TailArgs& a, unsigned* sync, int cus, void* stream)
+{
+    if (a.n_phases <= 0 || a.n_phases > kTailMaxPhases || !sync) return fail(SBN_EINVAL, "internal error: bad multi-layer launch");
+    // as many workgroups as the largest phase has tasks, and never more than are resident at once
+    // (two of these workgroups fit a compute unit; one per unit is asked for)
+    long long want = 1;
+    for (int p = 0; p < a.n_phases; ++p) {
+        const TailPhase& ph = a.ph[p];
+        long long tasks;
+        if (ph.kind == 1)
+            tasks = ((ph.M + 63) / 64) * ph.n_bundles;
+        else if (ph.kind == 0)
+            tasks = ((long long)ph.n * ph.oh * ph.ow * (ph.c / 4) + 64 * kTailWaves - 1) / (64 * kTailWaves);
+        else
+            tasks = (ph.M + 64 * kTailWaves - 1) / (64 * kTailWaves);
+        want = std::max(want, tasks);
+    }
+    const int grid = (int)std::min<long long>(want, cus);
+    hipLaunchKernelGGL(chain_tail_kernel, dim3(grid), dim3(64 * kTailWaves), 0, (hipStream_t)stream, a, sync, 1u << 20);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(SBN_EHIP, "multi-layer launch: %s", hipGetErrorString(e));
+    return SBN_OK;
+}
 
 int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, void* stream)
 {

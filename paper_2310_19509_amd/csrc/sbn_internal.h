@@ -131,6 +131,33 @@ int chain_device(const sbn_chain* c);
 int run_chain(const sbn_chain* c, const float* x, float* y, int n, int h, int w, void* workspace,
               size_t workspace_bytes, float* const* layer_outputs, void* stream, const char* who);
 
+// Several consecutive chain items in ONE launch, for inputs of few pixels where every launch
+// sits at the launch-latency floor: a grid of persistent workgroups runs the items as phases
+// with a grid-wide barrier between them (sbn_conv1x1.hip).  The phases travel by value as kernel
+// arguments.
+struct TailPhase {
+    int kind;                      // 0: depthwise 3x3, 1: group-sparse 1x1 (few-pixel form), 2: copy
+    int n, h, w, c, stride, act, oh, ow;         // depthwise: input extents and channels
+    const float* src;
+    float* dst;
+    const float* dw_w;             // depthwise [9][c], [c]
+    const float* dw_b;
+    const uint32_t* rec32;         // 1x1: the packed layer's tables per 32 channels
+    const uint32_t* woff32;
+    const float* wts;
+    const float* bias;
+    int K, N, n_bundles, n_chunks32;
+    long long M;                   // 1x1: pixels; copy: 16-byte words
+};
+constexpr int kTailMaxPhases = 24;
+struct TailArgs {
+    int n_phases;
+    TailPhase ph[kTailMaxPhases];
+};
+// sync: three device words {arrivals, generation, status}, zero when allocated; status != 0 after
+// a barrier wait ran into its spin limit (the launch then ends early and later ones do nothing).
+int launch_chain_tail(const TailArgs& a, unsigned* sync, int cus, void* stream);
+
 // Block l1 norms in the exact summation order the pruning rule is defined with.
 void block_norms(const float* w, int c_out, int kh, int kw, int c_in, int go, int gi, std::vector<double>& out);
 bool is_permutation(const int32_t* p, int n);

@@ -25,6 +25,7 @@ int launch_stem3x3(const float*, float*, const float*, const float*, int, int, i
 int launch_avgpool(const float*, float*, int, int, int, void*) { return unreachable("avgpool"); }
 int launch_copy(const void*, void*, size_t, void*) { return unreachable("copy"); }
 int static_workspace_init(int) { return SBN_OK; }
+int launch_chain_tail(const TailArgs&, unsigned*, int, void*) { return unreachable("chain tail"); }
 bool dwpw_fusable(const sbn_packed*, int, int) { return false; }
 int launch_dwpw(const sbn_packed*, const float*, float*, const float*, const float*, int, int, int, int, int, void*) { return unreachable("dwpw"); }
 }  // namespace sbn

@@ -421,3 +421,76 @@ def test_whole_mobilenet_batch64_full_size_sampled():
             assert_within_bound(out, ref, bound, f"mobilenet batch 64 item {i} ({m['kind']})")
         prev = out
     assert torch.equal(taps[-1], yd)
+
+
+def _teacher_forced(meta, outs, x):
+    prev = x
+    for i, m in enumerate(meta):
+        ref, bound = oracle_item(m, prev)
+        assert_within_bound(outs[i], ref, bound, f"multi-layer item {i} ({m['kind']})")
+        prev = outs[i]
+
+
+@pytest.mark.parametrize("n,hw", [(1, 14), (2, 9), (1, 7)])
+def test_runs_of_small_items_go_out_as_one_launch(n, hw):
+    """Few pixels (the paper's single-image setting): consecutive depthwise and 1x1 items run as
+    phases of ONE launch with grid-wide barriers in between (opt-in).  Every item's output is captured
+    (copies are phases of the same launch) and compared with the oracle fed with the GPU's previous
+    output; the final output must also agree with the one-launch-per-item path, and the chain's
+    barrier state must report no give-up."""
+    chans, strides = [128, 256, 256, 512], [1, 2, 1]
+    items, meta = build_stack(chans, hw, n, 50, 9900 + hw, strides)
+    chain = S.sbn_chain_create(items)
+    S.sbn_chain_set_multi_layer(chain, True)
+    x = W.uniform_activation(9950 + hw, (n, hw, hw, chans[0]))
+    xd = torch.from_numpy(x).cuda()
+    shapes, h, c = [], hw, chans[0]
+    for m in meta:
+        if m["kind"] == "dw":
+            h = (h - 1) // m["stride"] + 1
+        else:
+            c = m["w"].shape[0]
+        shapes.append((n, h, h, c))
+    ws = torch.empty(S.sbn_chain_workspace(chain, n, hw, hw) // 4, device="cuda")
+    taps = [torch.full(s, float("nan"), device="cuda") for s in shapes]
+    y_multi = torch.full(shapes[-1], float("nan"), device="cuda")
+    S.sbn_pointwise_chain(chain, xd, y_multi, n, hw, hw, ws, layer_outputs=taps)
+    torch.cuda.synchronize()
+    S.sbn_chain_check(chain)
+    outs = [t.cpu().numpy() for t in taps]
+    assert np.array_equal(outs[-1], y_multi.cpu().numpy())
+    _teacher_forced(meta, outs, x)
+    # twice more without taps (the barrier words carry over from launch to launch), then item by item
+    y_again = torch.full(shapes[-1], float("nan"), device="cuda")
+    for _ in range(2):
+        S.sbn_pointwise_chain(chain, xd, y_again, n, hw, hw, ws)
+    torch.cuda.synchronize()
+    S.sbn_chain_check(chain)
+    assert torch.equal(y_again, y_multi)
+    S.sbn_chain_set_multi_layer(chain, False)
+    y_items = torch.full(shapes[-1], float("nan"), device="cuda")
+    S.sbn_pointwise_chain(chain, xd, y_items, n, hw, hw, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(y_multi.cpu().numpy(), y_items.cpu().numpy(), rtol=2e-4, atol=2e-5)
+
+
+def test_mobilenet_batch1_multi_layer_tail_matches_item_by_item():
+    """Whole MobileNet-v1 on one image: the items from the fourth depthwise layer on (at most 784
+    pixels each) leave as one launch; logits agree with the path of one launch per item."""
+    import bench
+    chain, meta = bench.build_mobilenet_chain(S, W, 50, max_iters=50)
+    S.sbn_chain_set_multi_layer(chain, True)
+    g = torch.Generator(device="cuda").manual_seed(4002)
+    xd = torch.rand((1, 224, 224, 3), device="cuda", generator=g) * 2 - 1
+    ws = torch.empty(S.sbn_chain_workspace(chain, 1, 224, 224) // 4, device="cuda")
+    y_multi = torch.full((1, 1, 1, 1000), float("nan"), device="cuda")
+    y_items = torch.full((1, 1, 1, 1000), float("nan"), device="cuda")
+    S.sbn_pointwise_chain(chain, xd, y_multi, 1, 224, 224, ws)
+    torch.cuda.synchronize()
+    S.sbn_chain_check(chain)
+    S.sbn_chain_set_multi_layer(chain, False)
+    S.sbn_pointwise_chain(chain, xd, y_items, 1, 224, 224, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y_multi).all()
+    scale = float(y_items.abs().max())
+    assert float((y_multi - y_items).abs().max()) <= 1e-4 * max(scale, 1.0)
