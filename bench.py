@@ -53,6 +53,8 @@ def parse():
     ap.add_argument("--no-fuse", action="store_true",
                     help="mobilenet: run every depthwise layer as its own launch (default: the first three run "
                          "inside the 1x1 layers that consume them)")
+    ap.add_argument("--no-group-order", action="store_true",
+                    help="keep the filter groups in the order the search (or the layer) gives them")
     ap.add_argument("--multi-layer", action="store_true",
                     help="mobilenet: runs of small items (few pixels) leave as one launch with grid-wide barriers "
                          "(slower than one launch per item on this machine; kept as a measurement)")
@@ -151,7 +153,7 @@ def run_roof(a, torch, S):
                                    "frac": None if peak is None else round(v / peak, 4), "traffic": None}}))
 
 
-def build_layers(S, W, batch, pct, go, rearrange, gi=4):
+def build_layers(S, W, batch, pct, go, rearrange, gi=4, order_groups=True):
     """Offline part of the path: rearrangement, magnitude pruning, packing."""
     import numpy as np
     tens = [W.pw_layer_tensors(3000, L, batch, with_x=False) for L in W.MOBILENET_V1_PW]
@@ -164,6 +166,10 @@ def build_layers(S, W, batch, pct, go, rearrange, gi=4):
         # layer's filters are searched with its channels already in that order.  The layers are
         # timed on inputs of their own (in the order they would arrive in), so nothing else changes.
         perms = S.sbn_rearrange(descs, [-1] + list(range(n - 1)), pct, seed=3000, max_iters=500)
+        # the order of the groups is free (same section): groups that keep the same input pieces
+        # go into the same 16 filters, which the kernels walk together
+        if order_groups:
+            perms = S.sbn_order_groups(descs, [-1] + list(range(n - 1)), pct, perms)
     else:
         perms = [None] * n
     packed = []
@@ -193,6 +199,7 @@ def build_mobilenet_chain(S, W, pct, go=4, seed=4000, max_iters=300, dw_pattern=
     # the classifier absorbs the last pointwise layer's order; its own output order is kept
     perms = S.sbn_rearrange(descs, [-1] + list(range(n)), pct, seed=seed, max_iters=max_iters,
                             keep_output_order=[0] * n + [1])
+    perms = S.sbn_order_groups(descs, [-1] + list(range(n)), pct, perms, keep_output_order=[0] * n + [1])
     items = [S.stem_item(t["stem"]["w"], t["stem"]["bias"], stride=W.STEM["stride"], act=S.SBN_ACT_RELU)]
     meta = [dict(kind="stem", w=t["stem"]["w"], b=t["stem"]["bias"], stride=W.STEM["stride"])]
     pin = None
@@ -396,6 +403,7 @@ def run_mobilenet(a, torch, S, W):
 
 def run_conv3x3(a, torch, S, W):
     """Config 5: ResNet-50-shaped 3x3 layers, batch 32, kernel-level group sparsity 70 %."""
+    import numpy as np
     B, pct = 32 if a.batch == 64 else a.batch, 70 if a.sparsity == 30 else a.sparsity
     layers, dense, flops, bytes_alg, xs, ys, hws = [], [], [], [], [], [], []
     for idx in range(len(W.RESNET50_3X3)):
@@ -403,8 +411,15 @@ def run_conv3x3(a, torch, S, W):
         if a.k3_pattern_share:
             t["w"] = S.sbn_conv3x3_pattern_apply(t["w"], S.sbn_conv3x3_pattern_select(t["w"], a.k3_pattern_share),
                                                  a.k3_pattern_share)
-        mask = S.sbn_prune_magnitude(t["w"], S.SBN_CONV3X3, a.go, 4, pct)
-        p = S.sbn_pack(S.SBN_CONV3X3, t["w"], a.go, 4, mask=mask, bias=t["bias"], act=S.SBN_ACT_RELU, device=0)
+        # the grouping of the filters stays the original one (no rearrangement for these isolated
+        # layers); only the order of whole groups is chosen for the kernel, which keeps every block
+        po = None
+        if not a.no_group_order:
+            po = S.sbn_order_groups([dict(kind=S.SBN_CONV3X3, w=t["w"], go=a.go, gi=4)], [-1], pct,
+                                    [np.arange(t["c"], dtype=np.int32)])[0]
+        wp = t["w"] if po is None else np.ascontiguousarray(t["w"][po])
+        mask = S.sbn_prune_magnitude(wp, S.SBN_CONV3X3, a.go, 4, pct)
+        p = S.sbn_pack(S.SBN_CONV3X3, t["w"], a.go, 4, mask=mask, bias=t["bias"], perm_out=po, act=S.SBN_ACT_RELU, device=0)
         layers.append(p)
         if not a.no_dense:
             dense.append(S.sbn_pack(S.SBN_CONV3X3, t["w"], a.go, 4, bias=t["bias"], act=S.SBN_ACT_RELU, device=0))
@@ -463,7 +478,8 @@ def run_conv3x3(a, torch, S, W):
         "unit": "GFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"4 ResNet-50-shaped 3x3 convs (C 64..512, spatial 56..7), batch {B}, fp32, "
-                               f"kernel-level group sparsity {pct}% (go={a.go} gi=4 whole kernels)"
+                               f"kernel-level group sparsity {pct}% (go={a.go} gi=4 whole kernels"
+                               f"{'' if a.no_group_order else ', original grouping, groups in bundle order'})"
                                + (f", 4-of-9 patterns inside kept kernels shared by {a.k3_pattern_share} filters "
                                   "(stored zeros are multiplied and counted)" if a.k3_pattern_share else ""), "batch": B,
                    "sparsity_percent": pct},
@@ -516,7 +532,7 @@ def run_sweep(a, torch, S, W):
     for go, gi in ((4, 4), (8, 4), (8, 8)):          # 4x4 (the paper's choice), 8 filters x 4 channels, 8x8 (Table 1)
         base = None
         for pct in (0, 30, 50, 70, 90):
-            _, _, packed, _ = build_layers(S, W, B, pct, go, pct > 0 and not a.no_rearrange, gi=gi)
+            _, _, packed, _ = build_layers(S, W, B, pct, go, pct > 0 and not a.no_rearrange, gi=gi, order_groups=not a.no_group_order)
             fl = sum(2.0 * S.sbn_packed_work(p)["macs_per_pixel"] * B * L.hw * L.hw
                      for L, p in zip(W.MOBILENET_V1_PW, packed))
             ms_serial = run(packed, [main_s], a.steps, a.warmup)
@@ -562,7 +578,7 @@ def main():
     if a.workload in ("mfma_roof", "lds_roof", "hbm_read"):
         return run_roof(a, torch, S)
     B = a.batch
-    tens, perms, packed, pack_ms = build_layers(S, W, B, a.sparsity, a.go, not a.no_rearrange)
+    tens, perms, packed, pack_ms = build_layers(S, W, B, a.sparsity, a.go, not a.no_rearrange, order_groups=not a.no_group_order)
     dense = [] if a.no_dense else [S.sbn_pack(S.SBN_CONV1X1, t["w"], a.go, 4, bias=t["bias"], act=S.SBN_ACT_RELU,
                                               device=0) for t in tens]
 
@@ -645,7 +661,7 @@ def main():
     if not a.no_dense and a.sparsity == 30:
         speedup_by_sparsity[30] = round(speedup, 3)
         for pct in (50, 70, 90):
-            _, _, pk, _ = build_layers(S, W, B, pct, a.go, not a.no_rearrange)
+            _, _, pk, _ = build_layers(S, W, B, pct, a.go, not a.no_rearrange, order_groups=not a.no_group_order)
             ratios = []
             for _ in range(3):
                 ts = timed(pk, a.steps, a.warmup)[0]

@@ -224,6 +224,27 @@ int sbn_rearrange_graph(const sbn_layer_desc_t* layers, int n_layers, const int*
                         int32_t* const* perm_per_tensor_out);
 
 /*
+ * Order of the filter groups (Section 3.4: which filters share a group is what
+ * the rearrangement decides; the order of the groups makes no difference to
+ * the method, so it is chosen for the machine).  The device kernels walk 16
+ * consecutive filters together over the union of the 4-channel input pieces
+ * that any of them keeps at `sparsity_percent` (magnitude pruning, as
+ * sbn_prune_magnitude); this call reorders whole groups so that groups that
+ * keep the same pieces sit in the same 16.  Greedy and deterministic; the
+ * grouping, hence every mask, the retained importance and the network's
+ * function, is unchanged.  Whole units of max(go of the writers, gi of the
+ * readers) filters are moved so that the readers' blocks stay whole.
+ * The perms are read and rewritten in place: pass the result of sbn_rearrange /
+ * sbn_rearrange_graph (or identities); arguments as in those calls.
+ * SBN_EPERM if an order passed in is not a permutation.
+ */
+int sbn_order_groups(const sbn_layer_desc_t* layers, int n_layers, const int* parent,
+                     const int* keep_output_order, int sparsity_percent, int32_t* const* perm_per_layer_inout);
+int sbn_order_groups_graph(const sbn_layer_desc_t* layers, int n_layers, const int* in_tensor, const int* out_tensor,
+                           int n_tensors, const int* tensor_fixed, int sparsity_percent,
+                           int32_t* const* perm_per_tensor_inout);
+
+/*
  * Pack one layer into the group-sparse format (Algorithm 1's "sparse info":
  * per output group the first input channel of every kept block) and, when
  * device >= 0, build the device copy on that HIP device.  device = -1 packs on

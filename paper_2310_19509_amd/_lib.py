@@ -67,6 +67,10 @@ SYMBOLS = {
                                 C.c_uint64, C.c_int, C.POINTER(C.c_void_p)]),
     "sbn_rearrange_graph": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int,
                                       C.POINTER(C.c_int), C.c_int, C.c_uint64, C.c_int, C.POINTER(C.c_void_p)]),
+    "sbn_order_groups": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int,
+                                   C.POINTER(C.c_void_p)]),
+    "sbn_order_groups_graph": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int), C.c_int,
+                                         C.POINTER(C.c_int), C.c_int, C.POINTER(C.c_void_p)]),
     "sbn_pack": (C.c_int, [C.POINTER(LayerDesc), C.c_int, C.POINTER(C.c_void_p)]),
     "sbn_unpack": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "sbn_export": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,

@@ -12,7 +12,7 @@ from ._lib import ChainItem, LayerDesc
 __all__ = [
     "SBN_CONV1X1", "SBN_CONV3X3", "SBN_ACT_NONE", "SBN_ACT_RELU",
     "SBN_ITEM_SPARSE", "SBN_ITEM_DW3X3", "SBN_ITEM_AVGPOOL", "SbnError", "Packed", "Chain",
-    "sbn_last_error", "sbn_prune_magnitude", "sbn_retained_l1", "sbn_rearrange", "sbn_rearrange_graph", "sbn_pack", "sbn_unpack",
+    "sbn_last_error", "sbn_prune_magnitude", "sbn_retained_l1", "sbn_rearrange", "sbn_rearrange_graph", "sbn_order_groups", "sbn_order_groups_graph", "sbn_pack", "sbn_unpack",
     "sbn_export", "sbn_packed_info", "sbn_packed_work", "sbn_free", "sbn_conv1x1_sparse", "sbn_conv3x3_sparse",
     "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_pointwise_chain_static",
     "SBN_STATIC_WORKSPACE_BYTES", "sbn_chain_free",
@@ -250,6 +250,59 @@ def sbn_rearrange_graph(layers: Sequence[dict], in_tensor: Sequence[int], out_te
     _check(_lib.lib().sbn_rearrange_graph(descs, n, (C.c_int * n)(*in_tensor), (C.c_int * n)(*out_tensor), n_tensors,
                                           fixed, sparsity_percent, seed, max_iters, pp))
     return perms
+
+
+def _perm_copies(perms, sizes):
+    out = [np.ascontiguousarray(p, dtype=np.int32).copy() for p in perms]
+    for p, c in zip(out, sizes):
+        if p.shape != (c,):
+            raise ValueError(f"an order of length {c} is expected, got shape {p.shape}")
+    return out
+
+
+def sbn_order_groups(layers: Sequence[dict], parent: Sequence[int], sparsity_percent: int, perms: Sequence[np.ndarray],
+                     keep_output_order: Optional[Sequence[int]] = None) -> List[np.ndarray]:
+    """Reorders whole filter groups of the given per-layer orders (copies are returned)."""
+    n = len(layers)
+    descs = (LayerDesc * n)()
+    keep = []
+    for i, l in enumerate(layers):
+        d, k = _desc(l["kind"], l["w"], l["go"], l["gi"])
+        descs[i] = d
+        keep.append(k)
+    if len(perms) != n:
+        raise ValueError("one order per layer is expected")
+    out = _perm_copies(perms, [descs[i].c_out for i in range(n)])
+    koo = None if keep_output_order is None else (C.c_int * n)(*keep_output_order)
+    pp = (C.c_void_p * n)(*[p.ctypes.data for p in out])
+    _check(_lib.lib().sbn_order_groups(descs, n, (C.c_int * n)(*parent), koo, sparsity_percent, pp))
+    return out
+
+
+def sbn_order_groups_graph(layers: Sequence[dict], in_tensor: Sequence[int], out_tensor: Sequence[int], n_tensors: int,
+                           sparsity_percent: int, perms: Sequence[np.ndarray],
+                           tensor_fixed: Optional[Sequence[int]] = None) -> List[np.ndarray]:
+    """Reorders whole filter groups of the given per-tensor orders (copies are returned)."""
+    n = len(layers)
+    descs = (LayerDesc * n)()
+    keep = []
+    chans = [0] * n_tensors
+    for i, l in enumerate(layers):
+        d, k = _desc(l["kind"], l["w"], l["go"], l["gi"])
+        descs[i] = d
+        keep.append(k)
+        if 0 <= in_tensor[i] < n_tensors:
+            chans[in_tensor[i]] = d.c_in
+        if 0 <= out_tensor[i] < n_tensors:
+            chans[out_tensor[i]] = d.c_out
+    if len(perms) != n_tensors:
+        raise ValueError("one order per tensor is expected")
+    out = _perm_copies(perms, [max(c, 1) for c in chans])
+    pp = (C.c_void_p * n_tensors)(*[p.ctypes.data for p in out])
+    fixed = None if tensor_fixed is None else (C.c_int * n_tensors)(*tensor_fixed)
+    _check(_lib.lib().sbn_order_groups_graph(descs, n, (C.c_int * n)(*in_tensor), (C.c_int * n)(*out_tensor), n_tensors,
+                                             fixed, sparsity_percent, pp))
+    return out
 
 
 def sbn_pack(kind: int, w, go: int, gi: int, mask=None, bias=None, perm_out=None, perm_in=None, stride: int = 1,

@@ -701,6 +701,191 @@ static int sbn_rearrange_impl(const sbn_layer_desc_t* layers, int n_layers, cons
                                     ptrs.data());
 }
 
+// Order of the filter groups of every tensor (the grouping itself stays as it is).  The kernels
+// walk 16 consecutive filters (a bundle) together over the union of the 4-channel input pieces
+// that any of them keeps, so the groups that keep the same pieces belong next to each other.
+// Greedy: a bundle is opened by the unit with the most kept pieces and filled with the units
+// that add the fewest new pieces (ties: the most shared pieces, then the lower position); then
+// two units of different bundles are exchanged wherever that shrinks the two unions.  A unit
+// is max(go of the writers, gi of the readers) filters, so that every reader's blocks stay whole.
+static int sbn_order_groups_graph_impl(const sbn_layer_desc_t* layers, int n_layers, const int* in_tensor,
+                                       const int* out_tensor, int n_tensors, const int* tensor_fixed, int pct,
+                                       int32_t* const* perm)
+{
+    clear_error();
+    if (!layers || !in_tensor || !out_tensor || !perm || n_layers < 0 || n_tensors <= 0)
+        return fail(SBN_EINVAL, "sbn_order_groups_graph: NULL pointer or empty graph");
+    if (pct < 0 || pct > 100) return fail(SBN_EINVAL, "sparsity_percent must be in [0,100] (got %d)", pct);
+    std::vector<int> channels((size_t)n_tensors, 0);
+    for (int l = 0; l < n_layers; ++l) {
+        const sbn_layer_desc_t& d = layers[l];
+        if (!d.w) return fail(SBN_EINVAL, "sbn_order_groups_graph: layer %d has no weights", l);
+        if (int rc = check_geometry(d.kind, d.c_in, d.c_out, d.go, d.gi)) return rc;
+        const int ts[2] = {in_tensor[l], out_tensor[l]}, cs[2] = {d.c_in, d.c_out};
+        for (int k = 0; k < 2; ++k) {
+            if (ts[k] < 0 || ts[k] >= n_tensors) return fail(SBN_EINVAL, "layer %d: tensor %d is not in 0..%d", l, ts[k], n_tensors - 1);
+            if (channels[(size_t)ts[k]] && channels[(size_t)ts[k]] != cs[k])
+                return fail(SBN_ESHAPE, "tensor %d has %d channels but layer %d uses %d", ts[k], channels[(size_t)ts[k]], l, cs[k]);
+            channels[(size_t)ts[k]] = cs[k];
+        }
+    }
+    for (int t = 0; t < n_tensors; ++t) {
+        if (!channels[(size_t)t]) return fail(SBN_EINVAL, "tensor %d is used by no layer", t);
+        if (!perm[t]) return fail(SBN_EINVAL, "sbn_order_groups_graph: no order given for tensor %d", t);
+        if (!is_permutation(perm[t], channels[(size_t)t]))
+            return fail(SBN_EPERM, "the order given for tensor %d is not a permutation of 0..%d", t, channels[(size_t)t] - 1);
+    }
+    for (int t = 0; t < n_tensors; ++t) {
+        if (tensor_fixed && tensor_fixed[t]) continue;
+        const int c = channels[(size_t)t];
+        int unit = 0, go = 0;
+        for (int l = 0; l < n_layers; ++l) {
+            if (out_tensor[l] == t) {
+                if (go && layers[l].go != go)
+                    return fail(SBN_ESHAPE, "the layers that write tensor %d group their filters by %d and by %d", t, go, layers[l].go);
+                go = layers[l].go;
+            }
+        }
+        if (!go) continue;                                    // a network input
+        unit = go;
+        for (int l = 0; l < n_layers; ++l)
+            if (in_tensor[l] == t) unit = std::max(unit, layers[l].gi);
+        if (c % unit) continue;                               // (cannot happen: both divide c and are powers of two)
+        const int n_units = c / unit, per_bundle = 16 / unit;
+        if (n_units <= per_bundle) continue;
+        // kept 4-channel pieces of every unit, over all writers
+        std::vector<std::vector<uint64_t>> pieces((size_t)n_units);
+        size_t words = 0;
+        std::vector<float> wp;
+        std::vector<double> norms;
+        for (int l = 0; l < n_layers; ++l) {
+            if (out_tensor[l] != t) continue;
+            const sbn_layer_desc_t& d = layers[l];
+            const int k = d.kind == SBN_CONV3X3 ? 3 : 1, cols = d.c_in / d.gi, n_pieces = (d.c_in + 3) / 4;
+            permute_ohwi(d.w, d.c_out, k * k, d.c_in, perm[t], perm[in_tensor[l]], wp);
+            block_norms(wp.data(), d.c_out, k, k, d.c_in, d.go, d.gi, norms);
+            if (!all_finite(norms)) return fail(SBN_EINVAL, "sbn_order_groups_graph: the weights of layer %d contain NaN or infinity", l);
+            std::vector<uint32_t> order(norms.size());
+            std::iota(order.begin(), order.end(), 0u);
+            std::sort(order.begin(), order.end(),
+                      [&](uint32_t a, uint32_t b) { return norms[a] < norms[b] || (norms[a] == norms[b] && a < b); });
+            const size_t removed = removed_count(norms.size(), pct);
+            const size_t base = words, add = ((size_t)n_pieces + 63) / 64;
+            words += add;
+            for (auto& v : pieces) v.resize(words, 0);
+            for (size_t i = removed; i < order.size(); ++i) {
+                const int row = (int)(order[i] / (uint32_t)cols), col = (int)(order[i] % (uint32_t)cols);
+                std::vector<uint64_t>& v = pieces[(size_t)(row * d.go / unit)];
+                for (int ch = col * d.gi; ch < (col + 1) * d.gi; ch += 4 - ch % 4) v[base + (size_t)(ch / 4) / 64] |= 1ull << ((ch / 4) % 64);
+            }
+        }
+        auto count = [&](const std::vector<uint64_t>& a, const std::vector<uint64_t>* mask, bool in_mask) {
+            int nbits = 0;
+            for (size_t i = 0; i < words; ++i) {
+                uint64_t v = a[i];
+                if (mask) v &= in_mask ? (*mask)[i] : ~(*mask)[i];
+                nbits += __builtin_popcountll(v);
+            }
+            return nbits;
+        };
+        std::vector<char> used((size_t)n_units, 0);
+        std::vector<int> sequence;
+        std::vector<uint64_t> uni(words);
+        while ((int)sequence.size() < n_units) {
+            int seed_unit = -1, seed_count = -1;
+            for (int i = 0; i < n_units; ++i)
+                if (!used[(size_t)i]) {
+                    const int k = count(pieces[(size_t)i], nullptr, false);
+                    if (k > seed_count) seed_count = k, seed_unit = i;
+                }
+            used[(size_t)seed_unit] = 1;
+            sequence.push_back(seed_unit);
+            uni = pieces[(size_t)seed_unit];
+            for (int m = 1; m < per_bundle && (int)sequence.size() < n_units; ++m) {
+                int best = -1, best_new = 0, best_shared = 0;
+                for (int i = 0; i < n_units; ++i) {
+                    if (used[(size_t)i]) continue;
+                    const int fresh = count(pieces[(size_t)i], &uni, false), shared = count(pieces[(size_t)i], &uni, true);
+                    if (best < 0 || fresh < best_new || (fresh == best_new && shared > best_shared))
+                        best = i, best_new = fresh, best_shared = shared;
+                }
+                used[(size_t)best] = 1;
+                sequence.push_back(best);
+                for (size_t i = 0; i < words; ++i) uni[i] |= pieces[(size_t)best][i];
+            }
+        }
+        // then exchanges of two units of different bundles while the total shrinks (a few sweeps)
+        auto bundle_size = [&](int b) {
+            int nbits = 0;
+            for (size_t i = 0; i < words; ++i) {
+                uint64_t v = 0;
+                for (int m = b * per_bundle; m < std::min((b + 1) * per_bundle, n_units); ++m) v |= pieces[(size_t)sequence[(size_t)m]][i];
+                nbits += __builtin_popcountll(v);
+            }
+            return nbits;
+        };
+        const int n_bundles = (n_units + per_bundle - 1) / per_bundle;
+        std::vector<int> size_of((size_t)n_bundles);
+        for (int b = 0; b < n_bundles; ++b) size_of[(size_t)b] = bundle_size(b);
+        for (int sweep = 0, improved = 1; sweep < 8 && improved; ++sweep) {
+            improved = 0;
+            for (int i = 0; i < n_units; ++i)
+                for (int j = (i / per_bundle + 1) * per_bundle; j < n_units; ++j) {
+                    const int bi = i / per_bundle, bj = j / per_bundle;
+                    std::swap(sequence[(size_t)i], sequence[(size_t)j]);
+                    const int si = bundle_size(bi), sj = bundle_size(bj);
+                    if (si + sj < size_of[(size_t)bi] + size_of[(size_t)bj]) {
+                        size_of[(size_t)bi] = si;
+                        size_of[(size_t)bj] = sj;
+                        improved = 1;
+                    } else {
+                        std::swap(sequence[(size_t)i], sequence[(size_t)j]);
+                    }
+                }
+        }
+        std::vector<int32_t> old(perm[t], perm[t] + c);
+        for (int i = 0; i < n_units; ++i)
+            std::copy(old.begin() + (size_t)sequence[(size_t)i] * unit, old.begin() + (size_t)(sequence[(size_t)i] + 1) * unit,
+                      perm[t] + (size_t)i * unit);
+    }
+    return SBN_OK;
+}
+
+// The chain / tree form, tensors numbered as in sbn_rearrange_impl.
+static int sbn_order_groups_impl(const sbn_layer_desc_t* layers, int n_layers, const int* parent, const int* keep_output_order,
+                                 int pct, int32_t* const* perm)
+{
+    clear_error();
+    if (!layers || !parent || !perm || n_layers < 0) return fail(SBN_EINVAL, "sbn_order_groups: NULL pointer");
+    for (int l = 0; l < n_layers; ++l) {
+        if (!perm[l]) return fail(SBN_EINVAL, "sbn_order_groups: layer %d has a NULL pointer", l);
+        if (parent[l] >= l || parent[l] < -1) return fail(SBN_ESHAPE, "parent[%d] = %d: parents must come first", l, parent[l]);
+        if (parent[l] >= 0 && layers[parent[l]].c_out != layers[l].c_in)
+            return fail(SBN_ESHAPE, "layer %d reads %d channels but its parent %d writes %d", l, layers[l].c_in, parent[l],
+                        layers[parent[l]].c_out);
+        if (layers[l].c_in <= 0) return fail(SBN_EINVAL, "c_in and c_out must be positive");
+    }
+    std::vector<int> in_t((size_t)n_layers), out_t((size_t)n_layers), fixed;
+    int n_tensors = n_layers;
+    for (int l = 0; l < n_layers; ++l) {
+        out_t[(size_t)l] = l;
+        in_t[(size_t)l] = parent[l] >= 0 ? parent[l] : n_tensors++;
+    }
+    fixed.assign((size_t)n_tensors, 0);
+    for (int l = 0; l < n_layers; ++l) fixed[(size_t)l] = keep_output_order && keep_output_order[l] ? 1 : 0;
+    std::vector<std::vector<int32_t>> extra((size_t)(n_tensors - n_layers));
+    std::vector<int32_t*> ptrs((size_t)n_tensors);
+    for (int l = 0; l < n_layers; ++l) ptrs[(size_t)l] = perm[l];
+    for (int t = n_layers; t < n_tensors; ++t) {
+        std::vector<int32_t>& e = extra[(size_t)(t - n_layers)];
+        e.resize((size_t)layers[std::find(in_t.begin(), in_t.end(), t) - in_t.begin()].c_in);
+        std::iota(e.begin(), e.end(), 0);
+        ptrs[(size_t)t] = e.data();
+        fixed[(size_t)t] = 1;
+    }
+    return sbn_order_groups_graph_impl(layers, n_layers, in_t.data(), out_t.data(), n_tensors, fixed.data(), pct, ptrs.data());
+}
+
 static int sbn_pack_impl(const sbn_layer_desc_t* d, int device, sbn_packed_t** out)
 {
     clear_error();
@@ -895,6 +1080,21 @@ int sbn_rearrange_graph(const sbn_layer_desc_t* layers, int n_layers, const int*
     return guarded("sbn_rearrange_graph", [&]() -> int {
         return sbn_rearrange_graph_impl(layers, n_layers, in_tensor, out_tensor, n_tensors, tensor_fixed, pct, seed,
                                         max_iters, perm_per_tensor_out);
+    });
+}
+
+int sbn_order_groups(const sbn_layer_desc_t* layers, int n_layers, const int* parent, const int* keep_output_order,
+                     int pct, int32_t* const* perm_per_layer_inout)
+{
+    return guarded("sbn_order_groups", [&]() -> int { return sbn_order_groups_impl(layers, n_layers, parent, keep_output_order, pct, perm_per_layer_inout); });
+}
+
+int sbn_order_groups_graph(const sbn_layer_desc_t* layers, int n_layers, const int* in_tensor, const int* out_tensor,
+                           int n_tensors, const int* tensor_fixed, int pct, int32_t* const* perm_per_tensor_inout)
+{
+    return guarded("sbn_order_groups_graph", [&]() -> int {
+        return sbn_order_groups_graph_impl(layers, n_layers, in_tensor, out_tensor, n_tensors, tensor_fixed, pct,
+                                           perm_per_tensor_inout);
     });
 }
 

@@ -223,6 +223,16 @@ static int rearrangement()
         for (int s : seen) CHECK(s == 1);
     }
     for (int i = 0; i < cout[2]; ++i) CHECK(perm[2][(size_t)i] == i);          // kept output order
+    CHECK(sbn_order_groups(d, 3, parent, keep, 50, out) == SBN_OK);
+    for (int l = 0; l < 3; ++l) {
+        std::vector<int> seen((size_t)cout[l], 0);
+        for (int32_t v : perm[(size_t)l]) {
+            CHECK(v >= 0 && v < cout[l]);
+            ++seen[(size_t)v];
+        }
+        for (int s : seen) CHECK(s == 1);
+    }
+    for (int i = 0; i < cout[2]; ++i) CHECK(perm[2][(size_t)i] == i);
     const int bad_parent[3] = {-1, 2, 1};
     CHECK(sbn_rearrange(d, 3, bad_parent, keep, 50, 42, 10, out) != SBN_OK);   // parents must come first
     CHECK(sbn_rearrange(d, 3, parent, keep, 50, 42, 10, nullptr) == SBN_EINVAL);

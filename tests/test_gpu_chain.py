@@ -20,6 +20,7 @@ def build_stack(chans, hw, batch, pct, seed, strides):
            for i in range(L)]
     perms = S.sbn_rearrange(pws, [-1] + list(range(L - 1)), pct, seed=seed, max_iters=300,
                             keep_output_order=[0] * (L - 1) + [1])
+    perms = S.sbn_order_groups(pws, [-1] + list(range(L - 1)), pct, perms, keep_output_order=[0] * (L - 1) + [1])
     items, meta = [], []
     pin = None
     for i in range(L):

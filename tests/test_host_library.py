@@ -251,6 +251,77 @@ def test_rearrange_finds_planted_grouping():
     assert kinds == [0, 0, 4, 4]
 
 
+def _bundle_unions(w_run, go, gi, pct):
+    """Number of (bundle of 16 filters, 4-channel input piece) pairs with a kept block: what the
+    device kernels walk.  From the oracle's mask."""
+    m = R.prune_mask(w_run, go, gi, pct).astype(bool)
+    c_in = w_run.shape[3]
+    piece = np.zeros((m.shape[0], (c_in + 3) // 4), dtype=bool)
+    for j in range(m.shape[1]):
+        for ch in range(j * gi, (j + 1) * gi):
+            piece[:, ch // 4] |= m[:, j]
+    per = 16 // go
+    return sum(int(piece[b:b + per].any(axis=0).sum()) for b in range(0, piece.shape[0], per))
+
+
+def test_order_groups_keeps_the_grouping_and_shrinks_the_unions():
+    layers = _layers(391, [32, 64, 128, 64])
+    parent, keep = [-1, 0, 1], [0, 0, 1]
+    perms = S.sbn_rearrange(layers, parent, 70, seed=5, max_iters=300, keep_output_order=keep)
+    ordered = S.sbn_order_groups(layers, parent, 70, perms, keep_output_order=keep)
+    again = S.sbn_order_groups(layers, parent, 70, perms, keep_output_order=keep)
+    assert np.array_equal(ordered[2], np.arange(64))
+    before = after = 0
+    pin_a = pin_b = None
+    for l, p, q, q2 in zip(layers, perms, ordered, again):
+        assert np.array_equal(q, q2)
+        assert R.is_permutation(q, l["w"].shape[0])
+        # same groups (as sets), only their order differs
+        assert np.array_equal(R.canonicalize(q, 4), R.canonicalize(p, 4))
+        wa, wb = R.permute_weights(l["w"], p, pin_a), R.permute_weights(l["w"], q, pin_b)
+        assert math.isclose(R.retained_l1(wa, 4, 4, 70), R.retained_l1(wb, 4, 4, 70), rel_tol=1e-12)
+        before += _bundle_unions(wa, 4, 4, 70)
+        after += _bundle_unions(wb, 4, 4, 70)
+        pin_a, pin_b = p, q
+    assert after < before
+
+
+def test_order_groups_finds_planted_bundles():
+    """Eight groups, alternately keeping the first and the second half of the input pieces: the
+    groups of a kind belong in one bundle, which halves what a bundle walks."""
+    rng = np.random.default_rng(392)
+    w = (0.01 * rng.standard_normal((32, 1, 1, 64))).astype(np.float32)
+    for g in range(8):
+        half = slice(0, 32) if g % 2 == 0 else slice(32, 64)
+        w[g * 4:(g + 1) * 4, :, :, half] += rng.choice([-1.0, 1.0], (4, 1, 1, 32)).astype(np.float32)
+    layer = [dict(kind=S.SBN_CONV1X1, w=w, go=4, gi=4)]
+    ident = [np.arange(32, dtype=np.int32)]
+    assert _bundle_unions(w, 4, 4, 50) == 32
+    q = S.sbn_order_groups(layer, [-1], 50, ident)[0]
+    assert _bundle_unions(w[q], 4, 4, 50) == 16
+    kinds = [sorted((int(f) // 4) % 2 for f in q[b:b + 16]) for b in (0, 16)]
+    assert kinds[0][0] == kinds[0][-1] and kinds[1][0] == kinds[1][-1]
+
+
+def test_order_groups_moves_whole_blocks_of_the_readers():
+    """A reader with 8-channel blocks: filters move in runs of 8, so its blocks (hence its mask and
+    retained importance) stay what they were."""
+    w0, w1 = W.he_weights(393, 64, 1, 1, 32), W.he_weights(394, 32, 1, 1, 64)
+    layers = [dict(kind=S.SBN_CONV1X1, w=w0, go=4, gi=4), dict(kind=S.SBN_CONV1X1, w=w1, go=4, gi=8)]
+    ident = [np.arange(64, dtype=np.int32), np.arange(32, dtype=np.int32)]
+    q = S.sbn_order_groups(layers, [-1, 0], 60, ident, keep_output_order=[0, 1])
+    runs = q[0].reshape(8, 8)
+    assert np.array_equal(runs, runs[:, :1] + np.arange(8)) and np.all(runs[:, 0] % 8 == 0)
+    assert not np.array_equal(q[0], ident[0])
+    assert math.isclose(R.retained_l1(R.permute_weights(w1, None, q[0]), 4, 8, 60), R.retained_l1(w1, 4, 8, 60), rel_tol=1e-12)
+    # graph form, two writers of one tensor: same result as the chain form for a single writer
+    g = S.sbn_order_groups_graph(layers, [2, 0], [0, 1], 3, 60, [ident[0], ident[1], np.arange(32, dtype=np.int32)],
+                                 tensor_fixed=[0, 1, 1])
+    assert np.array_equal(g[0], q[0]) and np.array_equal(g[1], ident[1])
+    bad = [np.zeros(64, dtype=np.int32), ident[1]]
+    _err(lambda: S.sbn_order_groups(layers, [-1, 0], 60, bad), -3)
+
+
 def test_rearrange_errors():
     layers = _layers(371, [16, 32, 16])
     _err(lambda: S.sbn_rearrange(layers, [-1, 1], 50), -2)
