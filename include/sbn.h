@@ -344,7 +344,13 @@ typedef struct {
     int c_out;                  /* SBN_ITEM_STEM3X3: output channels, multiple of 4, <= 64  */
     const uint8_t* dw_pattern;  /* SBN_ITEM_DW3X3: NULL (dense) or one 3:9 pattern id per
                                    group of the layer's channels IN THE ORDER IT RUNS IN (the
-                                   rearranged order); the weights are masked accordingly    */
+                                   rearranged order); the weights are masked accordingly.
+                                   With groups of 16 the per-group kept taps also go to the
+                                   device: where the layer runs inside the 1x1 launch that
+                                   consumes it, a wave works on one group and loads and
+                                   multiplies only the six kept taps (Algorithm 2's dispatch
+                                   on the pattern); the stand-alone depthwise kernel is bound
+                                   by memory traffic and multiplies the stored zeros         */
     int dw_go;                  /* SBN_ITEM_DW3X3 with dw_pattern: group size (4, 8 or 16)   */
 } sbn_chain_item_t;
 

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cstring>
 #include <memory>
 #include <new>
 
@@ -18,6 +19,7 @@ struct sbn_chain {
         int channels = 0, stride = 1, act = 0, c_out = 0;
         float* d_w = nullptr;      // depthwise: [9][channels] in the arriving channel order
         float* d_b = nullptr;      // depthwise: [channels]
+        uint32_t* d_taps = nullptr;  // depthwise with 3:9 patterns in groups of 16: kept taps (9 bits) per group
     };
     std::vector<Item> items;
     int device = 0;
@@ -201,7 +203,7 @@ int run_chain(const sbn_chain* c, const float* x, float* y, int n, int h, int w,
             const bool last2 = i + 2 == c->items.size();
             float* dst2 = last2 ? y : buf[which];
             const Shape o2 = next_shape(pw, next_shape(it, s));
-            int rc2 = launch_dwpw(pw.packed, src, dst2, it.d_w, it.d_b, it.stride, it.act, (int)s.n, s.h, s.w, stream);
+            int rc2 = launch_dwpw(pw.packed, src, dst2, it.d_w, it.d_b, it.d_taps, it.stride, it.act, (int)s.n, s.h, s.w, stream);
             if (rc2) return rc2;
             if (layer_outputs && layer_outputs[i + 1]) {
                 if (o2.bytes() % 16) return fail(SBN_EINVAL, "output of item %zu is not a multiple of 16 bytes", i + 1);
@@ -306,6 +308,7 @@ static int chain_create_impl(const sbn_chain_item_t* items, int n_items, int dev
             it.act = s.act;
             cur_c = s.channels;
             dw_floats += (size_t)10 * s.channels;
+            if (s.dw_pattern && s.dw_go == 16 && s.channels % 16 == 0) dw_floats += (size_t)(s.channels / 16 + 3) / 4 * 4;
         } else if (s.item == SBN_ITEM_STEM3X3) {
             if (i != 0) { return fail(SBN_ESHAPE, "the stem convolution must be the first item of a chain"); }
             if (s.channels < 1 || s.channels > 4 || s.c_out <= 0 || s.c_out % 4 || s.c_out > 64 || !s.dw_w ||
@@ -362,8 +365,11 @@ static int chain_create_impl(const sbn_chain_item_t* items, int n_items, int dev
             }
             if (it.item != SBN_ITEM_DW3X3) continue;
             const int ch_n = it.channels;
-            // 3:9 pattern groups are formed over the channels in the order the layer runs in; the
-            // masked weights go through the dense kernel: the layer is bound by HBM, not by its taps
+            // 3:9 pattern groups are formed over the channels in the order the layer runs in.  The
+            // weights are masked here, so every kernel is right whatever it does with the pattern:
+            // the stand-alone depthwise kernel multiplies the zeros (it is bound by HBM, not by its
+            // taps); the kernel that computes the depthwise layer inside a 1x1 launch skips the
+            // removed taps of groups of 16, from the per-group tap masks built below.
             std::vector<uint8_t> pat_of_channel((size_t)ch_n, (uint8_t)SBN_DW_PATTERN_DENSE);
             if (items[i].dw_pattern) {
                 std::vector<int> st;
@@ -383,6 +389,20 @@ static int chain_create_impl(const sbn_chain_item_t* items, int n_items, int dev
             it.d_w = blob + off;
             it.d_b = blob + off + (size_t)9 * ch_n;
             off += (size_t)10 * ch_n;
+            if (items[i].dw_pattern && items[i].dw_go == 16 && ch_n % 16 == 0) {
+                static_assert(sizeof(uint32_t) == sizeof(float), "tap masks live in the float blob");
+                for (int g = 0; g < ch_n / 16; ++g) {
+                    const int pid = items[i].dw_pattern[g];
+                    uint32_t taps = 0x1FFu;
+                    if (pid != SBN_DW_PATTERN_DENSE) {
+                        taps = 0;
+                        for (int r = 0; r < 3; ++r) taps |= ((pid >> r) & 1 ? 3u : 6u) << (3 * r);   // loses column 2 : loses column 0
+                    }
+                    std::memcpy(&host[off + (size_t)g], &taps, sizeof taps);
+                }
+                it.d_taps = (uint32_t*)(blob + off);
+                off += (size_t)(ch_n / 16 + 3) / 4 * 4;
+            }
         }
         e = hipMemcpy(blob, host.data(), dw_floats * sizeof(float), hipMemcpyHostToDevice);
         (void)hipSetDevice(prev);

@@ -12,12 +12,18 @@
 //      before the previous sub-chunk is multiplied;
 //   2. every thread computes the depthwise outputs of one or two vertically adjacent pixels x 4
 //      channels (weights and bias of the whole layer sit in LDS) and writes them to the activation tile
-//      X[64 pixels][32 channels] that the 1x1 arithmetic reads;
+//      X[64 pixels][32 channels] that the 1x1 arithmetic reads.  For a layer with 3:9 pattern
+//      groups of 16 channels (Section 3.2, DwConv3x3; Algorithm 2's per-group pattern information;
+//      template parameter PAT) a wave works on ONE 16-channel half of the sub-chunk, which is one
+//      pattern group: the group's kept taps are a wave-uniform word, and one scalar branch picks
+//      the body that loads and multiplies only those six taps;
 //   3. the wave walks the bundle's entries of the sub-chunk exactly as the 1x1 kernel does: a
 //      16-byte LDS read per entry, 4 v_mfma_f32_4x4x1 per present group.
 // Used when the 1x1 layer has at most 128 input and 128 output channels; wider layers are bound by
 // the matrix pipe, not by memory traffic, and keep the two launches.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "sbn_internal.h"
 
@@ -60,10 +66,11 @@ struct Record8 {
     uint32_t d[8];
 };
 
-template <int STRIDE, int NWV>
+template <int STRIDE, int NWV, bool PAT>
 __global__ __launch_bounds__(64 * NWV) void dwpw_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                    const float* __restrict__ dw_w, const float* __restrict__ dw_b,
-                                                   int dw_act, const uint32_t* __restrict__ records,
+                                                   const uint32_t* __restrict__ dw_taps, int dw_act,
+                                                   const uint32_t* __restrict__ records,
                                                    const uint32_t* __restrict__ woff, const float* __restrict__ wts,
                                                    const float* __restrict__ bias, int H, int W, int OH, int OW, int K,
                                                    int N, int n_bundles, int n_sub, int n_col_tiles, int tiles_x,
@@ -71,13 +78,14 @@ __global__ __launch_bounds__(64 * NWV) void dwpw_kernel(const float* __restrict_
 {
     constexpr int IW = (TW - 1) * STRIDE + 3, IH = (TH - 1) * STRIDE + 3;     // input tile
     constexpr int NPIX = IW * IH;
+    constexpr int NPIXP = NPIX + (6 - NPIX % 4) % 4;           // = 2 mod 4: the two halves of a pixel pair fill all banks
     constexpr int NSLOT = NPIX * (KC / 4);
     constexpr int NT = 64 * NWV;                               // threads
     constexpr int NL = (NSLOT + NT - 1) / NT;
     constexpr int OS = 16 * NWV + 4;                           // row stride of the output tile in floats
     constexpr int NO = 8 / NWV;                                // depthwise output pixels per thread
-    constexpr int ABUF = NPIX * KC, OBUF = 64 * OS;
-    __shared__ __attribute__((aligned(16))) float lds_a[ABUF > OBUF ? ABUF : OBUF];   // input tile; output tile at the end
+    constexpr int ABUF = PAT ? 2 * NPIXP * 16 : NPIX * KC, OBUF = 64 * OS;
+    __shared__ __attribute__((aligned(16))) float lds_a[ABUF > OBUF ? ABUF : OBUF];   // input tile [pixel][32], PAT: [16-channel half][pixel][16]; output tile at the end
     __shared__ __attribute__((aligned(16))) float lds_x[64 * XS];                     // depthwise result
     __shared__ __attribute__((aligned(16))) float lds_p[10 * KMAX];                   // depthwise weights [9][K], bias [K]
 
@@ -128,14 +136,19 @@ __global__ __launch_bounds__(64 * NWV) void dwpw_kernel(const float* __restrict_
         for (int i = 0; i < NL; ++i) {
             const int pix = i * (NT / 8) + (threadIdx.x >> 3);
             const v4f v = (inside >> i) & 1u ? stage_reg[i] : (v4f){0.f, 0.f, 0.f, 0.f};
-            if (pix < NPIX) *(v4f*)(lds_a + pix * KC + col4) = v;
+            if (pix < NPIX) {
+                if (PAT)
+                    *(v4f*)(lds_a + ((col4 >> 4) * NPIXP + pix) * 16 + (col4 & 15)) = v;
+                else
+                    *(v4f*)(lds_a + pix * KC + col4) = v;
+            }
         }
     };
 
     // ---- depthwise: thread t -> channels col4..col4+3 of the sub-chunk, output pixels (oyp .. oyp +
     //      NO - 1, oxp) of the tile; the (NO - 1) * STRIDE + 3 input rows under them are read once
     const int oxp = (threadIdx.x >> 3) & 7, oyp = (threadIdx.x >> 6) * NO;
-    auto dw_compute = [&](int sc) {
+    auto dw_dense = [&](int sc) {
         const int ch = sc * KC + col4;
         v4f wt[9];
 #pragma unroll
@@ -170,6 +183,83 @@ __global__ __launch_bounds__(64 * NWV) void dwpw_kernel(const float* __restrict_
             }
             *(v4f*)(lds_x + ((oyp + jo) * TW + oxp) * XS + col4) = v;
         }
+    };
+
+    // ---- depthwise with pattern groups: a wave takes one 16-channel half of the sub-chunk (one group) and
+    //      2 * NO rows of the tile; lane -> channel quad, column, row pair.  Output pixels (oyp ..
+    //      oyp + NO - 1, oxp); the (NO - 1) * STRIDE + 3 input rows under them are read once.
+    const int half = wave & 1, quad4 = (lane & 3) * 4;
+    const int oxq = (lane >> 2) & 7, oyq = (wave >> 1) * (2 * NO) + (lane >> 5) * NO;
+    const float* aq = lds_a + (half * NPIXP + (oyq * STRIDE) * IW + oxq * STRIDE) * 16 + quad4;
+    float* xo = lds_x + (oyq * TW + oxq) * XS + half * 16 + quad4;
+    // TAPS: bit ky * 3 + kx set = the tap is kept by every channel of the group (removed taps hold
+    // zeros in dw_w, so a body that multiplies more taps than needed is still right)
+    auto dw_body = [&](int sc, auto taps_c) {
+        constexpr uint32_t TAPS = decltype(taps_c)::value;
+        const int ch = sc * KC + half * 16 + quad4;
+        const float* wp = lds_p + ch;                          // weights are read where they are used: few live registers
+        const v4f b = *(const v4f*)(lds_p + 9 * KMAX + ch);
+        v4f o[NO];
+#pragma unroll
+        for (int jo = 0; jo < NO; ++jo) o[jo] = b;
+#pragma unroll
+        for (int r = 0; r < (NO - 1) * STRIDE + 3; ++r) {
+            v4f a[3];
+#pragma unroll
+            for (int kx = 0; kx < 3; ++kx) {
+                bool needed = false;
+#pragma unroll
+                for (int jo = 0; jo < NO; ++jo) {
+                    const int ky = r - jo * STRIDE;
+                    if (ky >= 0 && ky < 3 && ((TAPS >> (ky * 3 + kx)) & 1u)) needed = true;
+                }
+                if (needed) a[kx] = *(const v4f*)(aq + (r * IW + kx) * 16);
+            }
+#pragma unroll
+            for (int jo = 0; jo < NO; ++jo) {
+                const int ky = r - jo * STRIDE;
+                if (ky >= 0 && ky < 3) {
+#pragma unroll
+                    for (int kx = 0; kx < 3; ++kx)
+                        if ((TAPS >> (ky * 3 + kx)) & 1u) o[jo] += *(const v4f*)(wp + (ky * 3 + kx) * K) * a[kx];
+                }
+            }
+        }
+#pragma unroll
+        for (int jo = 0; jo < NO; ++jo) {
+            v4f v = o[jo];
+            if (dw_act == SBN_ACT_RELU) {
+                v.x = fmaxf(v.x, 0.f);
+                v.y = fmaxf(v.y, 0.f);
+                v.z = fmaxf(v.z, 0.f);
+                v.w = fmaxf(v.w, 0.f);
+            }
+            *(v4f*)(xo + jo * TW * XS) = v;
+        }
+    };
+    // the 3:9 family: row r keeps columns {0, 1} (mask 3) or {1, 2} (mask 6)
+#define SBN_TAPS(R0, R1, R2) std::integral_constant<uint32_t, (R0) | ((R1) << 3) | ((R2) << 6)>()
+    auto dw_pattern = [&](int sc) {
+        const uint32_t taps = dw_taps ? __builtin_amdgcn_readfirstlane(dw_taps[sc * (KC / 16) + half]) : 0x1FFu;
+        switch (taps) {
+        case 6 | (6 << 3) | (6 << 6): dw_body(sc, SBN_TAPS(6, 6, 6)); break;
+        case 3 | (6 << 3) | (6 << 6): dw_body(sc, SBN_TAPS(3, 6, 6)); break;
+        case 6 | (3 << 3) | (6 << 6): dw_body(sc, SBN_TAPS(6, 3, 6)); break;
+        case 3 | (3 << 3) | (6 << 6): dw_body(sc, SBN_TAPS(3, 3, 6)); break;
+        case 6 | (6 << 3) | (3 << 6): dw_body(sc, SBN_TAPS(6, 6, 3)); break;
+        case 3 | (6 << 3) | (3 << 6): dw_body(sc, SBN_TAPS(3, 6, 3)); break;
+        case 6 | (3 << 3) | (3 << 6): dw_body(sc, SBN_TAPS(6, 3, 3)); break;
+        case 3 | (3 << 3) | (3 << 6): dw_body(sc, SBN_TAPS(3, 3, 3)); break;
+        default: dw_body(sc, SBN_TAPS(7, 7, 7)); break;
+        }
+    };
+#undef SBN_TAPS
+
+    auto dw_compute = [&](int sc) {
+        if constexpr (PAT)
+            dw_pattern(sc);
+        else
+            dw_dense(sc);
     };
 
     // ---- the 1x1 layer's tables: one record of 8 descriptors and one first-entry index per sub-chunk;
@@ -256,9 +346,9 @@ __global__ __launch_bounds__(64 * NWV) void dwpw_kernel(const float* __restrict_
     }
 }
 
-template <int STRIDE, int NWV>
-int launch(const sbn_packed* p, const float* x, float* y, const float* dw_w, const float* dw_b, int dw_act, int n, int h,
-           int w, hipStream_t st)
+template <int STRIDE, int NWV, bool PAT>
+int launch(const sbn_packed* p, const float* x, float* y, const float* dw_w, const float* dw_b, const uint32_t* dw_taps,
+           int dw_act, int n, int h, int w, hipStream_t st)
 {
     const sbn::DeviceLayout& L = p->dev;
     const int oh = (h - 1) / STRIDE + 1, ow = (w - 1) / STRIDE + 1;
@@ -270,7 +360,7 @@ int launch(const sbn_packed* p, const float* x, float* y, const float* dw_w, con
         return sbn::fail(SBN_EINVAL, "one image of %d x %d x %d elements is too large for 32-bit offsets", h, w, p->c_in);
     if (grid > 0x7FFFFFFFll || n_pix_tiles > 0x7FFFFFFFll)
         return sbn::fail(SBN_EINVAL, "too many output tiles for one launch (%lld)", n_pix_tiles);
-    hipLaunchKernelGGL((dwpw_kernel<STRIDE, NWV>), dim3((unsigned)grid), dim3(64 * NWV), 0, st, x, y, dw_w, dw_b, dw_act, L.d_records32,
+    hipLaunchKernelGGL((dwpw_kernel<STRIDE, NWV, PAT>), dim3((unsigned)grid), dim3(64 * NWV), 0, st, x, y, dw_w, dw_b, dw_taps, dw_act, L.d_records32,
                        L.d_woff32, L.d_wts, L.d_bias, h, w, oh, ow, p->c_in, p->c_out, L.n_bundles, L.n_chunks32, n_col_tiles,
                        tiles_x, tiles_y, (int)n_pix_tiles, p->act);
     hipError_t e = hipGetLastError();
@@ -288,17 +378,24 @@ bool dwpw_fusable(const sbn_packed* p, int channels, int stride)
            (stride == 1 || stride == 2);
 }
 
-int launch_dwpw(const sbn_packed* p, const float* x, float* y, const float* dw_w, const float* dw_b, int dw_stride,
-                int dw_act, int n, int h, int w, void* stream)
+int launch_dwpw(const sbn_packed* p, const float* x, float* y, const float* dw_w, const float* dw_b,
+                const uint32_t* dw_taps, int dw_stride, int dw_act, int n, int h, int w, void* stream)
 {
     if (!dwpw_fusable(p, p->c_in, dw_stride))
         return fail(SBN_EINVAL, "internal error: fused depthwise + 1x1 launch for a layer it does not cover");
     hipStream_t st = (hipStream_t)stream;
-    if (p->dev.n_bundles > 4)      // more than 64 output channels: eight waves cover up to 128
-        return dw_stride == 2 ? launch<2, 8>(p, x, y, dw_w, dw_b, dw_act, n, h, w, st)
-                              : launch<1, 8>(p, x, y, dw_w, dw_b, dw_act, n, h, w, st);
-    return dw_stride == 2 ? launch<2, 4>(p, x, y, dw_w, dw_b, dw_act, n, h, w, st)
-                          : launch<1, 4>(p, x, y, dw_w, dw_b, dw_act, n, h, w, st);
+    const bool wide = p->dev.n_bundles > 4;      // more than 64 output channels: eight waves cover up to 128
+#define SBN_DWPW(S, NWV, PAT) launch<S, NWV, PAT>(p, x, y, dw_w, dw_b, dw_taps, dw_act, n, h, w, st)
+    // Pattern bodies everywhere but in the eight-wave stride-2 form: there they need 134 registers,
+    // one workgroup per CU instead of two (109 us against 79 us for MobileNet-v1's second block at
+    // batch 64), so that form multiplies the stored zeros of the removed taps instead.
+    if (dw_taps && !(wide && dw_stride == 2)) {
+        if (wide) return SBN_DWPW(1, 8, true);
+        return dw_stride == 2 ? SBN_DWPW(2, 4, true) : SBN_DWPW(1, 4, true);
+    }
+    if (wide) return dw_stride == 2 ? SBN_DWPW(2, 8, false) : SBN_DWPW(1, 8, false);
+    return dw_stride == 2 ? SBN_DWPW(2, 4, false) : SBN_DWPW(1, 4, false);
+#undef SBN_DWPW
 }
 
 }  // namespace sbn

@@ -116,8 +116,9 @@ int launch_stem3x3(const float* x, float* y, const float* w_dev, const float* b_
                    int c_out, int stride, int act, void* stream);
 // depthwise 3x3 fused into the 1x1 layer that consumes it (small layers only: see dwpw_fusable)
 bool dwpw_fusable(const sbn_packed* p, int channels, int stride);
-int launch_dwpw(const sbn_packed* p, const float* x, float* y, const float* dw_w, const float* dw_b, int dw_stride,
-                int dw_act, int n, int h, int w, void* stream);
+// dw_taps: NULL, or per 16 channels (in running order) the 9-bit mask of the taps the group keeps
+int launch_dwpw(const sbn_packed* p, const float* x, float* y, const float* dw_w, const float* dw_b,
+                const uint32_t* dw_taps, int dw_stride, int dw_act, int n, int h, int w, void* stream);
 int launch_avgpool(const float* x, float* y, int n, int hw, int c, void* stream);
 int launch_copy(const void* src, void* dst, size_t bytes, void* stream);
 

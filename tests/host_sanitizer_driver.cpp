@@ -27,7 +27,7 @@ int launch_copy(const void*, void*, size_t, void*) { return unreachable("copy");
 int static_workspace_init(int) { return SBN_OK; }
 int launch_chain_tail(const TailArgs&, unsigned*, int, void*) { return unreachable("chain tail"); }
 bool dwpw_fusable(const sbn_packed*, int, int) { return false; }
-int launch_dwpw(const sbn_packed*, const float*, float*, const float*, const float*, int, int, int, int, int, void*) { return unreachable("dwpw"); }
+int launch_dwpw(const sbn_packed*, const float*, float*, const float*, const float*, const uint32_t*, int, int, int, int, int, void*) { return unreachable("dwpw"); }
 }  // namespace sbn
 
 static uint64_t g_state = 0x9E3779B97F4A7C15ull;

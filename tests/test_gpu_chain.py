@@ -303,23 +303,35 @@ FUSED_CASES = [
 ]
 
 
+@pytest.mark.parametrize("patterned", [False, True])
 @pytest.mark.parametrize("n,h,w,K,N,stride,pct,relu_dw,relu_pw,perm", FUSED_CASES)
-def test_depthwise_fused_into_small_pointwise_layer(n, h, w, K, N, stride, pct, relu_dw, relu_pw, perm):
+def test_depthwise_fused_into_small_pointwise_layer(n, h, w, K, N, stride, pct, relu_dw, relu_pw, perm, patterned):
     """A depthwise layer in front of a 1x1 layer with at most 128 channels on either side runs inside
     that layer's launch.  Checked against the oracle's two layers (the tolerance of the second carries
     the first's through the 1x1 weights: |err| <= 1e-4 (bound_pw + |W| bound_dw)), and against the
-    same chain with the fusion switched off."""
+    same chain with the fusion switched off.  patterned: the depthwise layer is 3:9 pattern pruned in
+    groups of 16 channels (one group left dense); the fused launch then skips the removed taps group
+    by group, and the oracle convolves the select-masked weights densely."""
     seed = 9700 + K + N + stride + pct
     dw_w = W.normal_weights(seed, (K, 3, 3), 0.4)
     dw_b = W.small_bias(seed + 1, K) * 10
+    pattern = None
+    if patterned:
+        keep_dense = np.zeros(K // 16, np.uint8)
+        keep_dense[K // 32] = 1
+        pattern = S.sbn_dw_pattern_select(dw_w, 16, keep_dense=keep_dense)
+        assert len(set(pattern.tolist())) >= 2
     wt = W.he_weights(seed + 2, N, 1, 1, K)
     b = W.small_bias(seed + 3, N) * 10
     po = W.random_permutation(seed + 4, N) if perm else None
     mask = S.sbn_prune_magnitude(R.permute_weights(wt, po, None), S.SBN_CONV1X1, 4, 4, pct)
     act_pw = S.SBN_ACT_RELU if relu_pw else S.SBN_ACT_NONE
     p = S.sbn_pack(S.SBN_CONV1X1, wt, 4, 4, mask=mask, bias=b, perm_out=po, act=act_pw)
-    chain = S.sbn_chain_create([S.dw_item(dw_w, dw_b, stride=stride, act=S.SBN_ACT_RELU if relu_dw else S.SBN_ACT_NONE),
+    chain = S.sbn_chain_create([S.dw_item(dw_w, dw_b, stride=stride, act=S.SBN_ACT_RELU if relu_dw else S.SBN_ACT_NONE,
+                                          pattern=pattern, go=16),
                                 S.sparse_item(p)])
+    if patterned:
+        dw_w = R.dw_pattern_apply(dw_w, pattern, 16)
     oh, ow, oc = S.sbn_chain_output_shape(chain, n, h, w)
     ws = torch.empty(S.sbn_chain_workspace(chain, n, h, w) // 4, device="cuda")
     x = W.uniform_activation(seed + 5, (n, h, w, K))
