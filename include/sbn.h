@@ -314,7 +314,11 @@ int sbn_conv3x3_sparse(const sbn_packed_t* p, const float* x, float* y,
  * beyond summation order.  kind: SBN_CONV1X1 (forms 11, 12, 14, 21, 22: pixels
  * per lane and accumulator sets; 504, 508, 516: 4, 8, 16 waves splitting the
  * input channels; 112, 121: forms 12 / 21 with the last pixel tiles run as
- * four-wave channel-splitting workgroups inside the same launch) or SBN_CONV3X3 (1, 2, 3: one pixel per lane, two pixels per
+ * four-wave channel-splitting workgroups inside the same launch; 1012, 1021,
+ * 1112, 1121: forms 12, 21, 112, 121 on the every-piece tables of layers that
+ * have them (sbn_packed_layout), the plain form otherwise -- forms below 1000
+ * never use those tables, the automatic choice always does; 1: the automatic
+ * choice without those tables) or SBN_CONV3X3 (1, 2, 3: one pixel per lane, two pixels per
  * lane, entry-ahead fetch; 32: entry-ahead with the input channels split over
  * two halves of an eight-wave workgroup).  Layers whose shape leaves no choice (c_in <= 64,
  * c_in not a multiple of 4, stride 2) ignore it.  Unknown values: SBN_EINVAL.
@@ -448,6 +452,16 @@ void sbn_chain_free(sbn_chain_t* c);
  * are 2 * macs_per_pixel * output pixels.
  */
 int sbn_packed_work(const sbn_packed_t* p, size_t* nnz_blocks_out, size_t* macs_per_pixel_out);
+
+/*
+ * What the kernels walk: the number of entries (a 4-channel input piece kept by
+ * at least one group of a bundle of 16 filters), the bytes of all tables and
+ * weights built for the device, and whether the layer also has the tables with
+ * an entry for every piece (1x1 layers of more than 64 input channels that keep
+ * at least 85 % of their (bundle, piece) pairs: the kernel then reads an entry's
+ * activations at a fixed offset).  Any output pointer may be NULL.
+ */
+int sbn_packed_layout(const sbn_packed_t* p, size_t* entries_out, size_t* table_bytes_out, int* every_piece_out);
 
 /*
  * Plain device-to-device copy kernel of `bytes` bytes (multiple of 16), used

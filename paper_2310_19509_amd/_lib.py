@@ -90,6 +90,7 @@ SYMBOLS = {
     "sbn_chain_check": (C.c_int, [C.c_void_p]),
     "sbn_chain_free": (None, [C.c_void_p]),
     "sbn_packed_work": (C.c_int, [C.c_void_p, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
+    "sbn_packed_layout": (C.c_int, [C.c_void_p, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_int)]),
     "sbn_copy_bytes": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "sbn_roof_mfma": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]),
     "sbn_roof_lds": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)]),

@@ -12,7 +12,7 @@ from ._lib import ChainItem, LayerDesc
 __all__ = [
     "SBN_CONV1X1", "SBN_CONV3X3", "SBN_ACT_NONE", "SBN_ACT_RELU",
     "SBN_ITEM_SPARSE", "SBN_ITEM_DW3X3", "SBN_ITEM_AVGPOOL", "SbnError", "Packed", "Chain",
-    "sbn_last_error", "sbn_prune_magnitude", "sbn_retained_l1", "sbn_rearrange", "sbn_rearrange_graph", "sbn_order_groups", "sbn_order_groups_graph", "sbn_pack", "sbn_unpack",
+    "sbn_last_error", "sbn_prune_magnitude", "sbn_retained_l1", "sbn_rearrange", "sbn_rearrange_graph", "sbn_order_groups", "sbn_order_groups_graph", "sbn_packed_layout", "sbn_pack", "sbn_unpack",
     "sbn_export", "sbn_packed_info", "sbn_packed_work", "sbn_free", "sbn_conv1x1_sparse", "sbn_conv3x3_sparse",
     "sbn_chain_create", "sbn_chain_workspace", "sbn_chain_output_shape", "sbn_pointwise_chain", "sbn_pointwise_chain_static",
     "SBN_STATIC_WORKSPACE_BYTES", "sbn_chain_free",
@@ -325,6 +325,12 @@ def sbn_packed_work(p: Packed) -> dict:
     nnz, macs = C.c_size_t(), C.c_size_t()
     _check(_lib.lib().sbn_packed_work(p.handle, C.byref(nnz), C.byref(macs)))
     return dict(nnz_blocks=nnz.value, macs_per_pixel=macs.value)
+
+
+def sbn_packed_layout(p: Packed) -> dict:
+    entries, nbytes, every = C.c_size_t(), C.c_size_t(), C.c_int()
+    _check(_lib.lib().sbn_packed_layout(p.handle, C.byref(entries), C.byref(nbytes), C.byref(every)))
+    return dict(entries=entries.value, table_bytes=nbytes.value, every_piece=bool(every.value))
 
 
 def sbn_unpack(p: Packed):

@@ -21,17 +21,30 @@
 // (16-byte loads per lane, four entries each) and the chunk's record of
 // descriptors (one scalar load) are fetched one chunk ahead.
 //
-// Epilogue: partial sums are added, bias and activation applied, the output
-// tile is transposed through LDS and written as full rows of 16-byte stores.
+// Epilogue: partial sums are added (the first one started from the bias), the
+// activation applied, the output tile is transposed through LDS and written as
+// full rows of 16-byte stores.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "sbn_internal.h"
 
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+
+// max(v, 0) per component as ONE instruction each: a signed integer maximum on the bit patterns
+// (a float with its sign bit set is a negative integer; -0.0 and negative NaNs become +0.0).
+// fmaxf() costs two (the compiler first re-quiets its operand), and every VALU instruction takes
+// matrix-pipe issue time.
+__device__ __forceinline__ v4f relu4(v4f v)
+{
+    typedef int v4i __attribute__((ext_vector_type(4)));
+    const v4i b = __builtin_bit_cast(v4i, v);
+    return __builtin_bit_cast(v4f, (v4i){b.x > 0 ? b.x : 0, b.y > 0 ? b.y : 0, b.z > 0 ? b.z : 0, b.w > 0 ? b.w : 0});
+}
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 // Vector instructions share their issue port with the matrix instructions: a plain VALU
@@ -118,13 +131,21 @@ struct Record {
 // One tile of the workgroup form: 64*P pixels x 64 output channels (four bundles, one per wave),
 // all input channels.  lds / lds_b: the workgroup's two activation buffers of 64*P x (KC+4)
 // floats each (lds_b unused when !MULTI).  Called by all 256 threads of the workgroup.
-template <int P, int NA, int KC, bool MULTI, bool VEC>
+//
+// STATIC: the layer's every-piece tables (layers that keep most of their pieces).  Entry q of a
+// chunk is piece q, present or not: `records` is then the array of present masks (s_stride per
+// bundle), `wts` the every-piece weights, `woff` is not used; the activations of entry q sit at a
+// compile-time offset of the lane's row, which takes the one VALU instruction per entry (the
+// address add) out of the loop -- it shares the issue port with the MFMAs.
+template <int P, int NA, int KC, bool MULTI, bool VEC, bool STATIC = false>
 __device__ __forceinline__ void plain_tile(float* __restrict__ lds, float* __restrict__ lds_b,
                                            const float* __restrict__ x, float* __restrict__ y,
                                            const uint32_t* __restrict__ records, const uint32_t* __restrict__ woff,
                                            const float* __restrict__ wts, const float* __restrict__ bias, long long M,
-                                           int K, int N, int n_bundles, int n_chunks, int pix_tile, int col_tile, int act)
+                                           int K, int N, int n_bundles, int n_chunks, int pix_tile, int col_tile, int act,
+                                           int s_stride = 0)
 {
+    static_assert(!STATIC || (MULTI && VEC), "every-piece tables exist for multi-chunk layers with c_in % 4 == 0");
     constexpr int T = 64 * P;                  // pixels per workgroup
     constexpr int NS = KC / 4;                 // descriptors per record (one record per KC channels)
     constexpr int NW = NS / 4;                 // 16-byte weight loads per lane and chunk
@@ -137,13 +158,19 @@ __device__ __forceinline__ void plain_tile(float* __restrict__ lds, float* __res
     const bool active = bundle < n_bundles;
     const int bsafe = active ? bundle : 0;
 
+    // the first partial sum of every group starts from the bias (a lane's four accumulator
+    // components are four output channels): the epilogue then has no bias add
     v4f acc[P][4][NA];
 #pragma unroll
-    for (int p = 0; p < P; ++p)
+    for (int g = 0; g < 4; ++g) {
+        const v4f b = *(const v4f*)(bias + bsafe * 16 + g * 4);
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+        for (int p = 0; p < P; ++p)
 #pragma unroll
-            for (int a = 0; a < NA; ++a) acc[p][g][a] = (v4f){0.f, 0.f, 0.f, 0.f};
+            for (int a = 0; a < NA; ++a) acc[p][g][a] = a == 0 ? b : (v4f){0.f, 0.f, 0.f, 0.f};
+    }
+    // (Setting the accumulators with MFMAs instead -- bias x 1 + 0 and 0 x 0 + 0, eight MFMAs for
+    // 32 register writes -- was measured 1.5 % slower over the 13-layer pass.)
 
     // ---- activation staging.  Thread t moves slots t, t+256, ... of the tile's
     // T x (KC/4) 16-byte slots.  Rows past the last pixel repeat the last pixel
@@ -196,11 +223,13 @@ __device__ __forceinline__ void plain_tile(float* __restrict__ lds, float* __res
     // ---- weights and descriptors of one chunk.  NW 16-byte loads per lane cover
     // NS entries; entries past the chunk's own belong to later chunks or to the
     // array's slack and are never used.
-    const uint32_t* wo = woff + (size_t)bsafe * (n_chunks + 1);
-    const Record<NS>* recs = (const Record<NS>*)__builtin_assume_aligned(records, 4 * NS) + (size_t)bsafe * n_chunks;
+    const uint32_t* wo = STATIC ? nullptr : woff + (size_t)bsafe * (n_chunks + 1);
+    const Record<NS>* recs = STATIC ? (const Record<NS>*)__builtin_assume_aligned(records + (size_t)bsafe * s_stride, 4 * NS)
+                                    : (const Record<NS>*)__builtin_assume_aligned(records, 4 * NS) + (size_t)bsafe * n_chunks;
     const __amdgpu_buffer_rsrc_t wres = make_rsrc(wts, 0xFFFFFFFFu);     // (the launcher checks the array is below 4 GiB)
     auto load_weights = [&](int c, v4f (&w)[NW]) {
-        const uint32_t e0 = __builtin_amdgcn_readfirstlane(wo[c]);
+        const uint32_t e0 = STATIC ? (uint32_t)bsafe * (uint32_t)s_stride + (uint32_t)c * NS
+                                   : __builtin_amdgcn_readfirstlane(wo[c]);
 #pragma unroll
         for (int q4 = 0; q4 < NW; ++q4) w[q4] = buf_load(wres, (uint32_t)lane * 16u + q4 * 1024u, e0 * 256u);
     };
@@ -243,6 +272,41 @@ __device__ __forceinline__ void plain_tile(float* __restrict__ lds, float* __res
         __builtin_amdgcn_s_waitcnt(0xC07F | ((Q == 0 || Q + 1 >= NS ? 0 : P) << 8)); \
         entry_fma<P, NA, Q>(r_cur.d[Q % NS], w_cur[(Q / 4) % NW], XC, acc);    \
     }
+            // every-piece walk: no terminator, the row offset of entry Q is 16 * Q; a piece that no
+            // group keeps (rare where these tables are built) is skipped with one test
+            auto read_s = [&](auto q_c, v4f (&xv)[P]) {
+                constexpr int QQ = decltype(q_c)::value;
+#pragma unroll
+                for (int p = 0; p < P; ++p) xv[p] = *(const v4f*)(lds_lane + QQ * 16 + p * (64 * XS * 4));
+            };
+#define SBN_ENTRY_S(Q, XC, XN)                                                 \
+    if (Q < NS) {                                                              \
+        if (Q + 1 < NS) read_s(std::integral_constant<int, (Q + 1) % NS>(), XN); \
+        __builtin_amdgcn_s_waitcnt(0xC07F | ((Q == 0 || Q + 1 >= NS ? 0 : P) << 8)); \
+        if (__builtin_expect(r_cur.d[Q % NS] != 0, 1))                         \
+            entry_fma<P, NA, Q>(r_cur.d[Q % NS], w_cur[(Q / 4) % NW], XC, acc); \
+    }
+            if (STATIC) {
+                read_s(std::integral_constant<int, 0>(), xa);
+                SBN_ENTRY_S(0, xa, xb)
+                SBN_ENTRY_S(1, xb, xa)
+                SBN_ENTRY_S(2, xa, xb)
+                SBN_ENTRY_S(3, xb, xa)
+                SBN_ENTRY_S(4, xa, xb)
+                SBN_ENTRY_S(5, xb, xa)
+                SBN_ENTRY_S(6, xa, xb)
+                SBN_ENTRY_S(7, xb, xa)
+                SBN_ENTRY_S(8, xa, xb)
+                SBN_ENTRY_S(9, xb, xa)
+                SBN_ENTRY_S(10, xa, xb)
+                SBN_ENTRY_S(11, xb, xa)
+                SBN_ENTRY_S(12, xa, xb)
+                SBN_ENTRY_S(13, xb, xa)
+                SBN_ENTRY_S(14, xa, xb)
+                SBN_ENTRY_S(15, xb, xa)
+                goto chunk_done;
+            }
+#undef SBN_ENTRY_S
             read_x(r_cur.d[0], xa);
             SBN_ENTRY(0, xa, xb)
             SBN_ENTRY(1, xb, xa)
@@ -283,29 +347,32 @@ __device__ __forceinline__ void plain_tile(float* __restrict__ lds, float* __res
         chunk(0, lds, lds, w_a, w_b, r_a, r_b);
     }
 
-    // ---- epilogue: partial sums, bias, activation; the output tile is transposed
-    // through LDS in passes of KC channels (KC/16 waves each) and stored as full rows.
-    // (The barrier that ended the last chunk makes the tile memory reusable.)
+    // ---- epilogue: the output tile is transposed through LDS in passes of KC channels (KC/16
+    // waves each) and stored as full rows.  The accumulators go to LDS as they are (the store
+    // takes them straight from the accumulator registers: no copy, no VALU instruction); with two
+    // partial sums per group and two activation buffers the second sums go through the second
+    // buffer, and the threads that store a row add the two, apply the activation and store.
+    // (The bias is in the first partial sum.  The barrier that ended the last chunk makes the
+    // tile memory reusable.)
+    constexpr bool TWO = MULTI && NA == 2;
 #pragma unroll
     for (int h = 0; h < 64 / KC; ++h) {
         if (h) __syncthreads();
         if (active && wave / (KC / 16) == h) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const v4f b = *(const v4f*)(bias + bundle * 16 + g * 4);
 #pragma unroll
                 for (int p = 0; p < P; ++p) {
-                    v4f o = acc[p][g][0];
+                    const int at = (p * 64 + lane) * XS + (wave % (KC / 16)) * 16 + g * 4;
+                    if (TWO) {
+                        *(v4f*)(lds + at) = acc[p][g][0];
+                        *(v4f*)(lds_b + at) = acc[p][g][1];
+                    } else {
+                        v4f o = acc[p][g][0];
 #pragma unroll
-                    for (int a = 1; a < NA; ++a) o += acc[p][g][a];
-                    o += b;
-                    if (act == SBN_ACT_RELU) {
-                        o.x = fmaxf(o.x, 0.f);
-                        o.y = fmaxf(o.y, 0.f);
-                        o.z = fmaxf(o.z, 0.f);
-                        o.w = fmaxf(o.w, 0.f);
+                        for (int a = 1; a < NA; ++a) o += acc[p][g][a];
+                        *(v4f*)(lds + at) = o;
                     }
-                    *(v4f*)(lds + (p * 64 + lane) * XS + (wave % (KC / 16)) * 16 + g * 4) = o;
                 }
             }
         }
@@ -321,8 +388,10 @@ __device__ __forceinline__ void plain_tile(float* __restrict__ lds, float* __res
             const int slot = i * 256 + threadIdx.x;
             const int row = slot / C4, col = (slot % C4) * 4;
             const uint32_t off = ch_base + col < N ? ((uint32_t)row * (uint32_t)N + (uint32_t)(ch_base + col)) * 4u : 0xFFFFFFF0u;
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, *(const v4f*)(lds + row * XS + col)), yres,
-                                                   (int)off, 0, 2 /* slc: streaming */);
+            v4f o = *(const v4f*)(lds + row * XS + col);
+            if (TWO) o += *(const v4f*)(lds_b + row * XS + col);
+            if (act == SBN_ACT_RELU) o = relu4(o);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u, o), yres, (int)off, 0, 2 /* slc: streaming */);
         }
     }
 }
@@ -337,13 +406,13 @@ __device__ __forceinline__ void xcd_tile(int id, int n_col_tiles, int& pix_tile,
     col_tile = j % n_col_tiles;
 }
 
-template <int P, int NA, int KC, bool MULTI, bool VEC>
+template <int P, int NA, int KC, bool MULTI, bool VEC, bool STATIC = false>
 __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                       const uint32_t* __restrict__ records,
                                                       const uint32_t* __restrict__ woff,
                                                       const float* __restrict__ wts, const float* __restrict__ bias,
                                                       long long M, int K, int N, int n_bundles, int n_chunks,
-                                                      int n_col_tiles, int n_pix_tiles, int act)
+                                                      int n_col_tiles, int n_pix_tiles, int act, int s_stride)
 {
     constexpr int XBUF = 64 * P * (KC + 4);    // floats per activation buffer
     __shared__ __attribute__((aligned(16))) float lds[XBUF];
@@ -351,8 +420,8 @@ __global__ __launch_bounds__(256) void conv1x1_kernel(const float* __restrict__ 
     int pix_tile, col_tile;
     xcd_tile(blockIdx.x, n_col_tiles, pix_tile, col_tile);
     if (pix_tile >= n_pix_tiles) return;
-    plain_tile<P, NA, KC, MULTI, VEC>(lds, lds_b, x, y, records, woff, wts, bias, M, K, N, n_bundles, n_chunks, pix_tile,
-                                      col_tile, act);
+    plain_tile<P, NA, KC, MULTI, VEC, STATIC>(lds, lds_b, x, y, records, woff, wts, bias, M, K, N, n_bundles, n_chunks,
+                                              pix_tile, col_tile, act, s_stride);
 }
 
 // Few-pixel form.  With few pixels (batch 1, deep layers) the workgroup kernel above leaves most
@@ -473,12 +542,7 @@ __device__ __forceinline__ void splitk_tile(float* __restrict__ lds_pool, const 
 #pragma unroll
         for (int s = 1; s < NW; ++s) o += *(const v4f*)(lds_all[s] + row * XS + col);
         o += *(const v4f*)(bias + bundle * 16 + col);
-        if (act == SBN_ACT_RELU) {
-            o.x = fmaxf(o.x, 0.f);
-            o.y = fmaxf(o.y, 0.f);
-            o.z = fmaxf(o.z, 0.f);
-            o.w = fmaxf(o.w, 0.f);
-        }
+        if (act == SBN_ACT_RELU) o = relu4(o);
         const long long pix = pix0 + row;
         if (pix < M && bundle * 16 + col < N) *(v4f*)(y + pix * N + bundle * 16 + col) = o;
     }
@@ -504,16 +568,20 @@ __global__ __launch_bounds__(64 * NW) void conv1x1_splitk_kernel(const float* __
 // the workgroup form on pixel tiles [0, tail_tile0); the pixels after that are covered by
 // workgroups of the few-pixel form (one bundle, input channels split over the four waves), each
 // a quarter of a tile's work per SIMD, which the dispatcher spreads evenly at the end.
-template <int P, int NA, int KC>
+// (STATIC: the workgroup-form part walks the every-piece tables -- records = the masks, wts_plain =
+// the every-piece weights; the few-pixel part always uses the compact tables.)
+template <int P, int NA, int KC, bool STATIC = false>
 __global__ __launch_bounds__(256) void conv1x1_mixed_kernel(const float* __restrict__ x, float* __restrict__ y,
                                                             const uint32_t* __restrict__ records,
                                                             const uint32_t* __restrict__ woff,
+                                                            const float* __restrict__ wts_plain,
                                                             const uint32_t* __restrict__ records32,
                                                             const uint32_t* __restrict__ woff32,
                                                             const float* __restrict__ wts,
                                                             const float* __restrict__ bias, long long M, int K, int N,
                                                             int n_bundles, int n_chunks, int n_chunks32, int n_col_tiles,
-                                                            int n_plain, long long tail_pix0, int n_tail_tiles, int act)
+                                                            int n_plain, long long tail_pix0, int n_tail_tiles, int act,
+                                                            int s_stride)
 {
     constexpr int XBUF = 64 * P * (KC + 4);
     constexpr int POOL = 2 * XBUF > 4 * 64 * 36 ? 2 * XBUF : 4 * 64 * 36;
@@ -521,8 +589,8 @@ __global__ __launch_bounds__(256) void conv1x1_mixed_kernel(const float* __restr
     if ((int)blockIdx.x < n_plain) {
         int pix_tile, col_tile;
         xcd_tile(blockIdx.x, n_col_tiles, pix_tile, col_tile);      // n_plain covers whole groups of 8 pixel tiles
-        plain_tile<P, NA, KC, true, true>(pool, pool + XBUF, x, y, records, woff, wts, bias, M, K, N, n_bundles, n_chunks,
-                                          pix_tile, col_tile, act);
+        plain_tile<P, NA, KC, true, true, STATIC>(pool, pool + XBUF, x, y, records, woff, wts_plain, bias, M, K, N, n_bundles,
+                                                  n_chunks, pix_tile, col_tile, act, s_stride);
     } else {
         // the bundles of one pixel tile get ids that differ by multiples of 8: same XCD, shared L2
         const int id = blockIdx.x - n_plain;
@@ -651,7 +719,7 @@ int launch_splitk(const sbn_packed* p, const float* x, float* y, long long M, hi
     return SBN_OK;
 }
 
-template <int P, int NA, int KC, bool MULTI, bool VEC>
+template <int P, int NA, int KC, bool MULTI, bool VEC, bool STATIC = false>
 int launch(const sbn_packed* p, const float* x, float* y, long long M, hipStream_t st)
 {
     const sbn::DeviceLayout& L = p->dev;
@@ -659,10 +727,12 @@ int launch(const sbn_packed* p, const float* x, float* y, long long M, hipStream
     const int n_col_tiles = (L.n_bundles + 3) / 4;
     const long long grid = ((n_pix_tiles + 7) / 8) * 8 * n_col_tiles;
     if (grid > 0x7FFFFFFFll) return sbn::fail(SBN_EINVAL, "too many pixels for one launch (%lld)", M);
-    hipLaunchKernelGGL((conv1x1_kernel<P, NA, KC, MULTI, VEC>), dim3((unsigned)grid), dim3(256), 0, st, x, y,
-                       KC == 64 ? L.d_records : L.d_records32, KC == 64 ? L.d_woff : L.d_woff32, L.d_wts, L.d_bias, M,
+    if (STATIC && !L.d_desc_s) return sbn::fail(SBN_EINVAL, "internal error: the layer has no every-piece tables");
+    hipLaunchKernelGGL((conv1x1_kernel<P, NA, KC, MULTI, VEC, STATIC>), dim3((unsigned)grid), dim3(256), 0, st, x, y,
+                       STATIC ? L.d_desc_s : KC == 64 ? L.d_records : L.d_records32, KC == 64 ? L.d_woff : L.d_woff32,
+                       STATIC ? L.d_wts_s : L.d_wts, L.d_bias, M,
                        p->c_in, p->c_out, L.n_bundles, KC == 64 ? L.n_chunks : L.n_chunks32, n_col_tiles,
-                       (int)n_pix_tiles, p->act);
+                       (int)n_pix_tiles, p->act, L.n_chunks * sbn::kSlots);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return sbn::fail(SBN_EHIP, "conv1x1 launch: %s", hipGetErrorString(e));
     return SBN_OK;
@@ -670,7 +740,7 @@ int launch(const sbn_packed* p, const float* x, float* y, long long M, hipStream
 
 // Mixed launch: pixel tiles [0, plain_tiles) (a multiple of 8) in the workgroup form, the pixels
 // after them in the few-pixel form.
-template <int P, int NA, int KC>
+template <int P, int NA, int KC, bool STATIC = false>
 int launch_mixed(const sbn_packed* p, const float* x, float* y, long long M, long long plain_tiles, hipStream_t st)
 {
     const sbn::DeviceLayout& L = p->dev;
@@ -681,11 +751,13 @@ int launch_mixed(const sbn_packed* p, const float* x, float* y, long long M, lon
     const long long grid = n_plain + ((n_tail_tiles + 7) / 8) * 8 * L.n_bundles;
     if (plain_tiles % 8 || tail_pix0 > M) return sbn::fail(SBN_EINVAL, "internal error: bad split of a mixed launch");
     if (grid > 0x7FFFFFFFll) return sbn::fail(SBN_EINVAL, "too many pixels for one launch (%lld)", M);
-    hipLaunchKernelGGL((conv1x1_mixed_kernel<P, NA, KC>), dim3((unsigned)grid), dim3(256), 0, st, x, y,
-                       KC == 64 ? L.d_records : L.d_records32, KC == 64 ? L.d_woff : L.d_woff32, L.d_records32,
+    if (STATIC && !L.d_desc_s) return sbn::fail(SBN_EINVAL, "internal error: the layer has no every-piece tables");
+    hipLaunchKernelGGL((conv1x1_mixed_kernel<P, NA, KC, STATIC>), dim3((unsigned)grid), dim3(256), 0, st, x, y,
+                       STATIC ? L.d_desc_s : KC == 64 ? L.d_records : L.d_records32, KC == 64 ? L.d_woff : L.d_woff32,
+                       STATIC ? L.d_wts_s : L.d_wts, L.d_records32,
                        L.d_woff32, L.d_wts, L.d_bias, M, p->c_in, p->c_out, L.n_bundles,
                        KC == 64 ? L.n_chunks : L.n_chunks32, L.n_chunks32, n_col_tiles, (int)n_plain, tail_pix0,
-                       (int)n_tail_tiles, p->act);
+                       (int)n_tail_tiles, p->act, L.n_chunks * sbn::kSlots);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return sbn::fail(SBN_EHIP, "conv1x1 launch: %s", hipGetErrorString(e));
     return SBN_OK;
@@ -724,7 +796,8 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
     hipStream_t st = (hipStream_t)stream;
     const int K = p->c_in;
     // the kernels address the weights with 32-bit byte offsets
-    if ((p->dev.wts.size() + (size_t)kSlots * 64) * sizeof(float) >= 0xFFFFFFFFull)
+    if ((p->dev.wts.size() + (size_t)kSlots * 64) * sizeof(float) >= 0xFFFFFFFFull ||
+        p->dev.wts_s.size() * sizeof(float) >= 0xFFFFFFFFull)
         return fail(SBN_EINVAL, "the layer's device weights exceed 4 GiB");
     const int force = forced_kernel_form(SBN_CONV1X1);  // testing / benchmarking override
     if (K % 4) {
@@ -733,11 +806,15 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
         return launch<1, 2, 64, true, false>(p, x, y, M, st);
     }
     // one chunk (HBM-bound layers): 64-pixel tiles keep more workgroups, hence more loads, in flight
-    const bool p2 = force / 10 == 2;
+    const bool p2 = (force % 1000) / 10 == 2 && force != 1;
     if (K <= 32) return p2 ? launch<2, 1, 32, false, true>(p, x, y, M, st) : launch<1, 2, 32, false, true>(p, x, y, M, st);
     if (K <= 64) return p2 ? launch<2, 1, 64, false, true>(p, x, y, M, st) : launch<1, 2, 64, false, true>(p, x, y, M, st);
     const int cus = p->dev.cus;
-    int variant = force;
+    // forms 1000 + f: form f on the every-piece tables (f where the layer has none); the automatic
+    // choice uses them whenever the layer has them
+    const bool have_s = p->dev.d_desc_s != nullptr;
+    const bool stat = force ? force >= 1000 && have_s : have_s;
+    int variant = force == 1 ? 0 : force % 1000;        // 1: the automatic choice, but never the every-piece tables
     // few pixels (at most four 64-pixel x one-bundle workgroups per CU) and at least 256 input
     // channels -> one bundle per workgroup, input channels split over its waves: as many waves as
     // keep the launch within about four waves per SIMD and leave every wave at least two
@@ -757,6 +834,9 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
         const long long tiles = (M + px - 1) / px, w = tiles * n_col_tiles, rem = w % cus;
         if (rem && 2 * rem <= cus && w > cus && n_sub >= 4) {
             const long long plain_tiles = (w - rem) / n_col_tiles / 8 * 8;
+            if (stat)
+                return variant == 21 ? launch_mixed<2, 1, 32, true>(p, x, y, M, plain_tiles, st)
+                                     : launch_mixed<1, 2, 64, true>(p, x, y, M, plain_tiles, st);
             return variant == 21 ? launch_mixed<2, 1, 32>(p, x, y, M, plain_tiles, st)
                                  : launch_mixed<1, 2, 64>(p, x, y, M, plain_tiles, st);
         }
@@ -764,9 +844,14 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
     if (variant == 112 || variant == 121) {             // forced mixed forms: all but the last pixel tiles plain
         const int px = variant == 121 ? 128 : 64;
         const long long plain_tiles = ((M + px - 1) / px - 1) / 8 * 8;
+        if (stat)
+            return variant == 121 ? launch_mixed<2, 1, 32, true>(p, x, y, M, plain_tiles, st)
+                                  : launch_mixed<1, 2, 64, true>(p, x, y, M, plain_tiles, st);
         return variant == 121 ? launch_mixed<2, 1, 32>(p, x, y, M, plain_tiles, st)
                               : launch_mixed<1, 2, 64>(p, x, y, M, plain_tiles, st);
     }
+    if (stat && (variant == 21 || variant == 12 || variant == 0))
+        return variant == 21 ? launch<2, 1, 32, true, true, true>(p, x, y, M, st) : launch<1, 2, 64, true, true, true>(p, x, y, M, st);
     switch (variant) {
     case 11: return launch<1, 1, 64, true, true>(p, x, y, M, st);
     case 14: return launch<1, 4, 64, true, true>(p, x, y, M, st);

@@ -377,7 +377,7 @@ const char* sbn_last_error(void) { return sbn::g_err.c_str(); }
 int sbn_force_kernel_form(int kind, int form)
 {
     clear_error();
-    static const int forms1x1[] = {0, 11, 12, 14, 21, 22, 112, 121, 504, 508, 516}, forms3x3[] = {0, 1, 2, 3, 32};
+    static const int forms1x1[] = {0, 1, 11, 12, 14, 21, 22, 112, 121, 504, 508, 516, 1012, 1021, 1112, 1121}, forms3x3[] = {0, 1, 2, 3, 32};
     bool ok = false;
     if (kind == SBN_CONV1X1)
         for (int f : forms1x1) ok |= f == form;
@@ -1040,6 +1040,19 @@ int sbn_packed_work(const sbn_packed_t* p, size_t* nnz, size_t* macs)
     if (!p) return fail(SBN_EINVAL, "sbn_packed_work: NULL pointer");
     if (nnz) *nnz = p->kidx.size();
     if (macs) *macs = p->kidx.size() * (size_t)p->go * p->gi * p->kh * p->kw;
+    return SBN_OK;
+}
+
+int sbn_packed_layout(const sbn_packed_t* p, size_t* entries, size_t* table_bytes, int* every_piece)
+{
+    clear_error();
+    if (!p) return fail(SBN_EINVAL, "sbn_packed_layout: NULL pointer");
+    const DeviceLayout& L = p->dev;
+    if (entries) *entries = L.n_entries;
+    if (table_bytes)
+        *table_bytes = (L.records.size() + L.woff.size() + L.records32.size() + L.woff32.size() + L.desc_s.size()) * sizeof(uint32_t) +
+                       (L.wts.size() + L.wts_s.size() + L.bias_padded.size()) * sizeof(float);
+    if (every_piece) *every_piece = L.desc_s.empty() ? 0 : 1;
     return SBN_OK;
 }
 

@@ -56,6 +56,7 @@ constexpr int kBundleGroups = 4;                       // groups of 4 filters pe
 constexpr int kBundleChannels = 4 * kBundleGroups;     // 16 output channels per bundle
 constexpr int kChunk = 64;                             // input channels per record
 constexpr int kSlots = kChunk / 4;                     // descriptors per record
+constexpr double kStaticWalkMinFill = 0.85;            // share of (bundle, piece) pairs kept, from which the every-piece tables are built
 
 struct DeviceLayout {
     int n_bundles = 0;
@@ -70,6 +71,13 @@ struct DeviceLayout {
     std::vector<uint32_t> woff32;         // [n_bundles][n_chunks32 + 1]   kb4_in_chunk < 8
     std::vector<float> wts;
     std::vector<float> bias_padded;       // [n_bundles * 16], zeros when no bias
+    // 1x1 layers that keep most of their pieces (see kStaticWalkMinFill) also get the tables with an
+    // entry for EVERY piece, present or not: entry q of chunk c is piece q, so the kernel reads its
+    // activations at an offset known at compile time.  desc_s[bundle][n_chunks * 16]: the present
+    // mask of the piece (0 = no group keeps it); wts_s[bundle][n_chunks * 16][64]: as wts, zeros
+    // for absent pieces.  Empty when the layer does not qualify.
+    std::vector<uint32_t> desc_s;
+    std::vector<float> wts_s;
     // device copies (one allocation)
     void* d_blob = nullptr;
     uint32_t* d_records = nullptr;
@@ -78,6 +86,8 @@ struct DeviceLayout {
     uint32_t* d_woff32 = nullptr;
     float* d_wts = nullptr;
     float* d_bias = nullptr;
+    uint32_t* d_desc_s = nullptr;         // NULL when the layer has no every-piece tables
+    float* d_wts_s = nullptr;
 };
 
 }  // namespace sbn

@@ -82,6 +82,27 @@ void build_device_layout(sbn_packed* p)
         (void)first;
     }
     L.n_entries = n_entries;
+    // every-piece tables for 1x1 layers of more than one chunk that keep most of their pieces
+    L.desc_s.clear();
+    L.wts_s.clear();
+    const size_t n_pieces = (size_t)(p->c_in + 3) / 4;
+    if (taps == 1 && p->c_in > kChunk && p->c_in % 4 == 0 &&
+        (double)n_entries >= kStaticWalkMinFill * (double)((size_t)L.n_bundles * n_pieces)) {
+        const size_t per_bundle = (size_t)L.n_chunks * kSlots;
+        L.desc_s.assign((size_t)L.n_bundles * per_bundle, 0u);
+        L.wts_s.assign((size_t)L.n_bundles * per_bundle * 64, 0.0f);
+        for (int b = 0; b < L.n_bundles; ++b)
+            for (int c = 0; c < L.n_chunks; ++c) {
+                const uint32_t* r = &L.records[((size_t)b * L.n_chunks + c) * kSlots];
+                const size_t e0 = L.woff[(size_t)b * (L.n_chunks + 1) + c];
+                for (int q = 0; q < kSlots && r[q] != 0; ++q) {
+                    const size_t piece = (size_t)c * kSlots + (r[q] >> 12);
+                    L.desc_s[(size_t)b * per_bundle + piece] = r[q] & 0xFu;
+                    std::copy(L.wts.begin() + (e0 + q) * 64, L.wts.begin() + (e0 + q + 1) * 64,
+                              L.wts_s.begin() + ((size_t)b * per_bundle + piece) * 64);
+                }
+            }
+    }
     L.bias_padded.assign((size_t)L.n_bundles * kBundleChannels, 0.0f);
     std::copy(p->bias.begin(), p->bias.end(), L.bias_padded.begin());
 }
@@ -123,6 +144,20 @@ const char* check_device_layout(const sbn_packed* p)
     if (const char* e = check_tables(L.records32, L.woff32, L.n_bundles, L.n_chunks32, 8, L.n_entries)) return e;
     if (L.wts.size() != L.n_entries * (size_t)p->kh * p->kw * kBundleGroups * 16) return "weight array size";
     if (L.bias_padded.size() != (size_t)L.n_bundles * kBundleChannels) return "bias array size";
+    if (!L.desc_s.empty()) {
+        const size_t per_bundle = (size_t)L.n_chunks * kSlots;
+        if (p->kh != 1 || L.desc_s.size() != (size_t)L.n_bundles * per_bundle || L.wts_s.size() != L.desc_s.size() * 64)
+            return "every-piece table sizes";
+        size_t present = 0;
+        for (size_t i = 0; i < L.desc_s.size(); ++i) {
+            if (L.desc_s[i] > 15u) return "every-piece mask out of range";
+            if ((i % per_bundle) * 4 >= (size_t)p->c_in && L.desc_s[i] != 0) return "every-piece mask past the last channel";
+            present += L.desc_s[i] != 0;
+        }
+        if (present != L.n_entries) return "every-piece entry count";
+    } else if (!L.wts_s.empty()) {
+        return "every-piece weights without masks";
+    }
     return nullptr;
 }
 
@@ -150,7 +185,9 @@ int upload_device_layout(sbn_packed* p)
     const size_t b_woff32 = align256(L.woff32.size() * sizeof(uint32_t));
     const size_t b_wts = align256((L.wts.size() + kSlots * wstride) * sizeof(float));
     const size_t b_bias = align256(L.bias_padded.size() * sizeof(float));
-    const size_t total = b_rec + b_woff + b_rec32 + b_woff32 + b_wts + b_bias;
+    const size_t b_desc_s = align256(L.desc_s.size() * sizeof(uint32_t));
+    const size_t b_wts_s = align256(L.wts_s.size() * sizeof(float));
+    const size_t total = b_rec + b_woff + b_rec32 + b_woff32 + b_wts + b_bias + b_desc_s + b_wts_s;
     char* blob = nullptr;
     if ((e = hipMalloc((void**)&blob, total)) != hipSuccess) {
         (void)hipSetDevice(prev);
@@ -175,6 +212,16 @@ int upload_device_layout(sbn_packed* p)
     off += b_wts;
     std::memcpy(host.data() + off, L.bias_padded.data(), L.bias_padded.size() * sizeof(float));
     L.d_bias = (float*)(blob + off);
+    off += b_bias;
+    L.d_desc_s = nullptr;
+    L.d_wts_s = nullptr;
+    if (!L.desc_s.empty()) {
+        std::memcpy(host.data() + off, L.desc_s.data(), L.desc_s.size() * sizeof(uint32_t));
+        L.d_desc_s = (uint32_t*)(blob + off);
+        off += b_desc_s;
+        std::memcpy(host.data() + off, L.wts_s.data(), L.wts_s.size() * sizeof(float));
+        L.d_wts_s = (float*)(blob + off);
+    }
     e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
     (void)hipSetDevice(prev);
     if (e != hipSuccess) {

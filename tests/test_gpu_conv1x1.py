@@ -70,7 +70,7 @@ def test_shapes(n, h, w, K, N, go, gi, pct, use_bias, relu, perms):
         assert np.array_equal(y, np.broadcast_to(expect, y.shape))
 
 
-@pytest.mark.parametrize("variant", [11, 12, 14, 21, 22, 112, 121, 504, 508, 516])
+@pytest.mark.parametrize("variant", [11, 12, 14, 21, 22, 112, 121, 504, 508, 516, 1012, 1021, 1112, 1121])
 @pytest.mark.parametrize("n,h,w,K,N,pct", [(3, 9, 11, 128, 256, 30), (1, 7, 7, 512, 1024, 70), (2, 13, 5, 72, 40, 50),
                                              (1, 20, 20, 320, 64, 0), (1, 26, 50, 128, 96, 50)])
 def test_every_multi_chunk_kernel_form(variant, n, h, w, K, N, pct):
@@ -78,7 +78,9 @@ def test_every_multi_chunk_kernel_form(variant, n, h, w, K, N, pct):
     partial sums per group, 64- or 32-channel chunks, input channels split over waves, and the
     mixed forms 112 / 121 whose last pixel tiles run as few-pixel workgroups inside the same
     launch) chosen by launch size; each is forced in turn and must match the oracle on the same
-    input.  The 1300-pixel case gives the mixed forms 16 (8) whole tiles and a ragged remainder."""
+    input.  The 1300-pixel case gives the mixed forms 16 (8) whole tiles and a ragged remainder.
+    Forms above 1000 walk the every-piece tables, which layers at 0-50 % sparsity have and the
+    70 % layer has not (it then runs the plain form); 72 and 320 channels end in a ragged chunk."""
     seed = 7500 + K + N + pct
     wt = W.he_weights(seed, N, 1, 1, K)
     b = W.small_bias(seed + 1, N) * 20

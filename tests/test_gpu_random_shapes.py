@@ -11,7 +11,7 @@ from helpers import assert_within_bound
 
 pytestmark = pytest.mark.gpu
 
-FORMS = {S.SBN_CONV1X1: [0, 11, 12, 14, 21, 22, 112, 121, 504, 508, 516], S.SBN_CONV3X3: [0, 1, 2, 3, 32]}
+FORMS = {S.SBN_CONV1X1: [0, 11, 12, 14, 21, 22, 112, 121, 504, 508, 516, 1012, 1021, 1112, 1121], S.SBN_CONV3X3: [0, 1, 2, 3, 32]}
 
 
 def random_case(rng):
