@@ -458,7 +458,7 @@ int sbn_packed_work(const sbn_packed_t* p, size_t* nnz_blocks_out, size_t* macs_
  * at least one group of a bundle of 16 filters), the bytes of all tables and
  * weights built for the device, and whether the layer also has the tables with
  * an entry for every piece (1x1 layers of more than 64 input channels that keep
- * at least 85 % of their (bundle, piece) pairs: the kernel then reads an entry's
+ * at least 60 % of their (bundle, piece) pairs: the kernel then reads an entry's
  * activations at a fixed offset).  Any output pointer may be NULL.
  */
 int sbn_packed_layout(const sbn_packed_t* p, size_t* entries_out, size_t* table_bytes_out, int* every_piece_out);

@@ -56,7 +56,7 @@ constexpr int kBundleGroups = 4;                       // groups of 4 filters pe
 constexpr int kBundleChannels = 4 * kBundleGroups;     // 16 output channels per bundle
 constexpr int kChunk = 64;                             // input channels per record
 constexpr int kSlots = kChunk / 4;                     // descriptors per record
-constexpr double kStaticWalkMinFill = 0.85;            // share of (bundle, piece) pairs kept, from which the every-piece tables are built
+constexpr double kStaticWalkMinFill = 0.60;            // share of (bundle, piece) pairs kept, from which the every-piece tables are built
 
 struct DeviceLayout {
     int n_bundles = 0;

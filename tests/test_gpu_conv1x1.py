@@ -79,8 +79,8 @@ def test_every_multi_chunk_kernel_form(variant, n, h, w, K, N, pct):
     mixed forms 112 / 121 whose last pixel tiles run as few-pixel workgroups inside the same
     launch) chosen by launch size; each is forced in turn and must match the oracle on the same
     input.  The 1300-pixel case gives the mixed forms 16 (8) whole tiles and a ragged remainder.
-    Forms above 1000 walk the every-piece tables, which layers at 0-50 % sparsity have and the
-    70 % layer has not (it then runs the plain form); 72 and 320 channels end in a ragged chunk."""
+    Forms above 1000 walk the every-piece tables, which layers that keep at least 60 % of their
+    pieces have (a layer without them runs the plain form); 72 and 320 channels end in a ragged chunk."""
     seed = 7500 + K + N + pct
     wt = W.he_weights(seed, N, 1, 1, K)
     b = W.small_bias(seed + 1, N) * 20

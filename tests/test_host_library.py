@@ -137,6 +137,25 @@ def test_nonfinite_weights_and_device_3x3_channel_rule_are_refused():
     assert np.array_equal(wt.view(np.uint32), w3.view(np.uint32))
 
 
+def test_packed_layout_reports_entries_and_every_piece_tables():
+    """Entries = (bundle of 16 filters, 4-channel piece) pairs with a kept block, counted here from
+    the oracle's mask; the every-piece tables exist for 1x1 layers of more than 64 input channels
+    that keep at least 60 % of those pairs."""
+    w = W.he_weights(331, 64, 1, 1, 128)
+    for pct, expect in ((0, True), (50, True), (70, True), (90, False)):
+        mask = S.sbn_prune_magnitude(w, S.SBN_CONV1X1, 4, 4, pct)
+        lay = S.sbn_packed_layout(S.sbn_pack(S.SBN_CONV1X1, w, 4, 4, mask=mask, device=-1))
+        m = R.prune_mask(w, 4, 4, pct).astype(bool)
+        entries = sum(int(m[b:b + 4].any(axis=0).sum()) for b in range(0, m.shape[0], 4))
+        assert lay["entries"] == entries
+        assert lay["every_piece"] == expect, (pct, entries, 4 * 32)
+        assert lay["table_bytes"] > 0
+    small = S.sbn_pack(S.SBN_CONV1X1, W.he_weights(332, 32, 1, 1, 64), 4, 4, device=-1)      # one chunk: no such tables
+    assert not S.sbn_packed_layout(small)["every_piece"]
+    k3 = S.sbn_pack(S.SBN_CONV3X3, W.he_weights(333, 16, 3, 3, 128), 4, 4, device=-1)
+    assert not S.sbn_packed_layout(k3)["every_piece"]
+
+
 # ---------------------------------------------------------------- rearrangement
 
 def _layers(seed, chans, go=4, gi=4):
