@@ -25,10 +25,12 @@ PEAK_HBM_GBS = 8000.0             # MI355X published HBM3E bandwidth
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--workload", default="pw13", choices=["pw13", "mobilenet", "conv3x3", "sweep", "copy", "mfma_roof", "lds_roof", "hbm_read"],
+    ap.add_argument("--workload", default="pw13", choices=["pw13", "mobilenet", "conv3x3", "sweep", "forms", "copy", "mfma_roof", "lds_roof", "hbm_read"],
                     help="pw13: the 13 pointwise layers (headline metric); mobilenet: the whole network as one "
                          "chain, batch 64, 50 %% sparsity; conv3x3: ResNet-50-shaped 3x3 layers, batch 32, 70 %%; "
                          "sweep: the pointwise stack at 0/30/50/70/90 %% sparsity and go 4/8 against all groups kept; "
+                         "forms: every kernel form forced in turn on every layer of the two kernel workloads, against the "
+                         "form the launch rule picks (regenerates the evidence behind the rule's thresholds); "
                          "copy: the library's device copy kernel on 256 MiB (measured HBM roof, counter calibration); "
                          "mfma_roof / lds_roof / hbm_read: stand-alone loops that measure what the matrix pipe, LDS and "
                          "a read-only stream deliver on this machine")
@@ -151,6 +153,72 @@ def run_roof(a, torch, S):
                       "config": {"workload": a.workload},
                       "roofline": {"bound": bound, "achieved": v, "peak": peak, "unit": unit,
                                    "frac": None if peak is None else round(v / peak, 4), "traffic": None}}))
+
+
+def run_forms(a, torch, S, W):
+    """Every kernel form forced in turn on every layer of the pointwise stack (batch and sparsity
+    from the command line) and of the 3x3 layers (batch 32, 70 %): microseconds per launch, beside the form the launch rule picks (form 0); 0.2 s of untimed launches first on every layer,
+    100 timed launches after 10 per figure, medians of five interleaved rounds.  The launch rules
+    in the library count in compute units and were set from tables like this one."""
+    med = lambda v: sorted(v)[len(v) // 2]
+
+    def warm(fn):                                       # packing a layer on the host lets the GPU's clocks drop
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < 0.2:
+            for _ in range(50):
+                fn()
+            torch.cuda.synchronize()
+
+    out = {"conv1x1": [], "conv3x3": []}
+    forms1 = [0, 1, 12, 21, 112, 121, 1012, 1021, 1112, 1121, 504, 508]
+    B, pct = a.batch, a.sparsity
+    for L in W.MOBILENET_V1_PW:
+        if L.c_in <= 64:
+            continue                                   # one chunk: the shape leaves no choice
+        t = W.pw_layer_tensors(3000, L, B, with_x=False)
+        mask = S.sbn_prune_magnitude(t["w"], S.SBN_CONV1X1, a.go, 4, pct)
+        p = S.sbn_pack(S.SBN_CONV1X1, t["w"], a.go, 4, mask=mask, bias=t["bias"], act=S.SBN_ACT_RELU, device=0)
+        m = B * L.hw * L.hw
+        x, y = torch.rand((m, L.c_in), device="cuda"), torch.empty((m, L.c_out), device="cuda")
+        us = {f: [] for f in forms1}
+        warm(lambda: S.sbn_conv1x1_sparse(p, x, y, 1, 1, m))
+        for rnd in range(5):
+            for f in forms1[2 * rnd:] + forms1[:2 * rnd]:       # every form meets different neighbours
+                S.sbn_force_kernel_form(S.SBN_CONV1X1, f)
+                us[f].append(time_steps(torch, lambda: S.sbn_conv1x1_sparse(p, x, y, 1, 1, m), 100, 10) * 1e3)
+        S.sbn_force_kernel_form(S.SBN_CONV1X1, 0)
+        row = {str(f): round(med(v), 1) for f, v in us.items()}
+        best = min(row, key=row.get)
+        out["conv1x1"].append(dict(layer=L.index, pixels=m, c_in=L.c_in, c_out=L.c_out, us=row, best=best,
+                                   rule_within_percent_of_best=round(100 * (row["0"] / row[best] - 1), 1)))
+        S.sbn_free(p)
+    forms3 = [0, 1, 2, 3, 32]
+    for idx in range(len(W.RESNET50_3X3)):
+        t = W.conv3x3_layer_tensors(5000, idx, 32, with_x=False)
+        mask = S.sbn_prune_magnitude(t["w"], S.SBN_CONV3X3, 4, 4, 70)
+        p = S.sbn_pack(S.SBN_CONV3X3, t["w"], 4, 4, mask=mask, bias=t["bias"], act=S.SBN_ACT_RELU, device=0)
+        x = torch.rand((32, t["hw"], t["hw"], t["c"]), device="cuda")
+        y = torch.empty((32, t["hw"], t["hw"], t["c"]), device="cuda")
+        us = {f: [] for f in forms3}
+        warm(lambda: S.sbn_conv3x3_sparse(p, x, y, 32, t["hw"], t["hw"]))
+        for rnd in range(5):
+            for f in forms3[rnd:] + forms3[:rnd]:
+                S.sbn_force_kernel_form(S.SBN_CONV3X3, f)
+                us[f].append(time_steps(torch, lambda: S.sbn_conv3x3_sparse(p, x, y, 32, t["hw"], t["hw"]), 100, 10) * 1e3)
+        S.sbn_force_kernel_form(S.SBN_CONV3X3, 0)
+        row = {str(f): round(med(v), 1) for f, v in us.items()}
+        best = min(row, key=row.get)
+        out["conv3x3"].append(dict(c=t["c"], hw=t["hw"], us=row, best=best,
+                                   rule_within_percent_of_best=round(100 * (row["0"] / row[best] - 1), 1)))
+        S.sbn_free(p)
+    worst = max(r["rule_within_percent_of_best"] for k in out for r in out[k])
+    print(json.dumps({"metric": "launch rule against the best forced kernel form, worst layer", "value": worst, "unit": "percent slower",
+                      "n_gpus": 1, "steps": 100, "warmup": 10, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": f"every kernel form on the 1x1 layers (batch {B}, {pct} %) and the 3x3 layers (batch 32, 70 %)"},
+                      "forms": {"conv1x1": "0 rule, 1 rule without every-piece tables, 12/21 64-/128-pixel tiles, 112/121 the same with the "
+                                           "last round as few-pixel workgroups, 10xx/11xx on every-piece tables, 504/508 input channels split over 4/8 waves",
+                                "conv3x3": "0 rule, 1 one pixel per lane, 2 two pixels, 3 entry-ahead, 32 channel split"},
+                      "extra": out}))
 
 
 def build_layers(S, W, batch, pct, go, rearrange, gi=4, order_groups=True):
@@ -573,6 +641,8 @@ def main():
         return run_conv3x3(a, torch, S, W)
     if a.workload == "sweep":
         return run_sweep(a, torch, S, W)
+    if a.workload == "forms":
+        return run_forms(a, torch, S, W)
     if a.workload == "copy":
         return run_copy(a, torch, S)
     if a.workload in ("mfma_roof", "lds_roof", "hbm_read"):

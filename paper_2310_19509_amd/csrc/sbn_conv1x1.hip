@@ -826,8 +826,10 @@ int launch_conv1x1(const sbn_packed* p, const float* x, float* y, long long M, v
     const int n_col_tiles = (p->dev.n_bundles + 3) / 4;
     if (!variant) {
         // 128-pixel tiles with 32-channel chunks halve the per-entry overhead; they pay off
-        // when there are still several such tiles per CU
-        variant = ((M + 127) / 128) * n_col_tiles >= 6ll * cus ? 21 : 12;
+        // from three such tiles per CU on (timed with every form forced on every layer of the
+        // MobileNet stack at batch 64: 5-9 % over 64-pixel tiles at 3.06 tiles per CU, 15-20 %
+        // behind them at 1.6)
+        variant = ((M + 127) / 128) * n_col_tiles >= 3ll * cus ? 21 : 12;
         // Whole rounds of workgroups only: when the last round would occupy at most half of
         // the compute units, the pixels of that round go to few-pixel workgroups instead.
         const int px = variant == 21 ? 128 : 64;
