@@ -180,6 +180,35 @@ def test_full_size_batch64_sampled(layer_idx):
             S.sbn_free(p)
 
 
+def test_the_benchmarks_own_layers_at_full_size_sampled():
+    """The default benchmark's step itself: the 13 layers as bench.py builds them (filters rearranged
+    as a chain, groups ordered for the kernels, 30 % by block magnitude, batch 64), launched as the
+    benchmark launches them; every output channel of about 300 sampled pixels per layer against
+    the oracle on the same permuted, masked weights."""
+    import bench
+    tens, perms, packed, _ = bench.build_layers(S, W, 64, 30, 4, True)
+    pin = None
+    for L, t, po, p in zip(W.MOBILENET_V1_PW, tens, perms, packed):
+        m = 64 * L.hw * L.hw
+        g = torch.Generator(device="cuda").manual_seed(3100 + L.index)
+        xd = torch.rand((m, L.c_in), device="cuda", generator=g) * 2 - 1      # channels in perm_in order
+        rng = np.random.default_rng(100 + L.index)
+        idx = np.unique(np.concatenate([rng.integers(0, m, 200), np.arange(0, 32), np.arange(m - 64, m)]))
+        idx_d = torch.from_numpy(idx).cuda()
+        yd = torch.full((m, L.c_out), float("nan"), device="cuda")
+        S.sbn_conv1x1_sparse(p, xd, yd, 64, L.hw, L.hw)
+        torch.cuda.synchronize()
+        assert torch.isfinite(yd).all()
+        wp = R.permute_weights(t["w"], po, pin)
+        mask = R.prune_mask(wp, 4, 4, 30)
+        assert S.sbn_packed_work(p)["nnz_blocks"] == int(mask.sum())
+        # the oracle on the permuted layer: its input order is the order xd is in, its output order yd's
+        ref, bound = R.sparse_conv_reference(xd[idx_d].cpu().numpy()[None, None], wp, mask, 4, 4, bias=t["bias"][po],
+                                             act=S.SBN_ACT_RELU)
+        assert_within_bound(yd[idx_d].cpu().numpy()[None, None], ref, bound, f"bench layer pw{L.index}")
+        pin = po
+
+
 def test_config2_all_13_layers_batch1_rearranged_chained_perms():
     """Config 2: the 13 pointwise layers at batch 1, each on its own input, 30 % by block magnitude
     after rearrangement, permutations chained across the stack; every output is compared."""
