@@ -113,15 +113,22 @@ def test_pattern_pruned_kernels(share, stride):
     assert per_kernel.max() <= 4 and (per_kernel == 4).mean() > 0.99
 
 
+@pytest.mark.parametrize("ordered", [False, True])
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
-def test_resnet50_shapes_batch32_sampled(idx):
-    """Config 5: ResNet-50-shaped 3x3 layers at batch 32, 70 % kernel-group sparsity; sampled images."""
+def test_resnet50_shapes_batch32_sampled(idx, ordered):
+    """Config 5: ResNet-50-shaped 3x3 layers at batch 32, 70 % kernel-group sparsity; sampled images.
+    ordered: as the benchmark packs them, the original grouping with whole filter groups reordered
+    for the kernel (the output then comes in that order, and so does the oracle's)."""
     t = W.conv3x3_layer_tensors(5000, idx, 32, with_x=False)
     c, hw = t["c"], t["hw"]
+    po = None
+    if ordered:
+        po = S.sbn_order_groups([dict(kind=S.SBN_CONV3X3, w=t["w"], go=4, gi=4)], [-1], 70, [np.arange(c, dtype=np.int32)])[0]
+        assert np.array_equal(R.canonicalize(po, 4), np.arange(c))           # the grouping is the original one
     g = torch.Generator(device="cuda").manual_seed(5000 + idx)
     xd = torch.rand((32, hw, hw, c), device="cuda", generator=g) * 2 - 1
-    mask = S.sbn_prune_magnitude(t["w"], S.SBN_CONV3X3, 4, 4, 70)
-    p = S.sbn_pack(S.SBN_CONV3X3, t["w"], 4, 4, mask=mask, bias=t["bias"], act=S.SBN_ACT_RELU)
+    mask = S.sbn_prune_magnitude(R.permute_weights(t["w"], po, None), S.SBN_CONV3X3, 4, 4, 70)
+    p = S.sbn_pack(S.SBN_CONV3X3, t["w"], 4, 4, mask=mask, bias=t["bias"], perm_out=po, act=S.SBN_ACT_RELU)
     yd = torch.full((32, hw, hw, c), float("nan"), device="cuda")
     S.sbn_conv3x3_sparse(p, xd, yd, 32, hw, hw)
     torch.cuda.synchronize()
@@ -131,14 +138,14 @@ def test_resnet50_shapes_batch32_sampled(idx):
     ys = yd[imgs].cpu().numpy()
     if hw == 56:          # keep the oracle's work to seconds: the top and the bottom band of 16 rows
         # (each needs one extra input row on its inner side; the outer side is the image border)
-        ref, bound = R.sparse_conv_reference(xs[:, :17], t["w"], mask, 4, 4, bias=t["bias"], stride=1, pad=1,
+        ref, bound = R.sparse_conv_reference(xs[:, :17], t["w"], mask, 4, 4, bias=t["bias"], perm_out=po, stride=1, pad=1,
                                              act=S.SBN_ACT_RELU)
         assert_within_bound(ys[:, :16], ref[:, :16], bound[:, :16], f"resnet shape {idx} top rows")
         ref, bound = R.sparse_conv_reference(np.ascontiguousarray(xs[:, hw - 17:]), t["w"], mask, 4, 4, bias=t["bias"],
-                                             stride=1, pad=1, act=S.SBN_ACT_RELU)
+                                             perm_out=po, stride=1, pad=1, act=S.SBN_ACT_RELU)
         assert_within_bound(ys[:, hw - 16:], ref[:, 1:], bound[:, 1:], f"resnet shape {idx} bottom rows")
     else:
-        ref, bound = R.sparse_conv_reference(xs, t["w"], mask, 4, 4, bias=t["bias"], stride=1, pad=1,
+        ref, bound = R.sparse_conv_reference(xs, t["w"], mask, 4, 4, bias=t["bias"], perm_out=po, stride=1, pad=1,
                                              act=S.SBN_ACT_RELU)
         assert_within_bound(ys, ref, bound, f"resnet shape {idx}")
 
