@@ -24,6 +24,15 @@
 // Epilogue: partial sums are added (the first one started from the bias), the
 // activation applied, the output tile is transposed through LDS and written as
 // full rows of 16-byte stores.
+//
+// Forms (launch_conv1x1 picks one per launch): the workgroup form above with 64 or
+// 128 pixels per tile (plain_tile); the few-pixel form, one bundle per workgroup with
+// the input channels split over its waves (splitk_tile); the mixed launch, whole
+// rounds of workgroup tiles plus the remaining pixels as few-pixel workgroups in one
+// grid; and, for layers that keep most of their pieces, the walk over the
+// every-piece tables, where entry q of a chunk is piece q and its activations sit
+// at a compile-time offset.  chain_tail_kernel runs several small chain items as
+// phases of one launch.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -57,12 +66,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);   // raw, 32-bit words
 }
-// AUX = 16 (sc1): the access is coherent across the whole device -- it goes past the caches
-// that other XCDs do not see -- for data that workgroups hand to one another inside a launch.
-template <int AUX = 0>
 __device__ __forceinline__ v4f buf_load(__amdgpu_buffer_rsrc_t r, uint32_t lane_off, uint32_t scalar_off)
 {
-    return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)scalar_off, AUX));
+    return __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(r, (int)lane_off, (int)scalar_off, 0));
 }
 
 template <int ABID>
